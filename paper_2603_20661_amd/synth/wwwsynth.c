@@ -1,0 +1,74 @@
+/* Seeded synthetic-input generator shared by the CPU oracle's tests and the GPU path's tests.
+ *
+ * This file holds no transformer arithmetic: it only produces reproducible pseudo-random
+ * numbers (weights, token ids, lengths, permutations) from a counter-based hash, so that both
+ * sides of a parity test can be handed bit-identical inputs.
+ *
+ * Definition of the stream (seed, stream_id):
+ *   key      = mix(seed ^ mix(stream_id))
+ *   word(c)  = mix(key + c * 0x9E3779B97F4A7C15)          c = 0, 1, 2, ...
+ * where mix is the 64-bit finaliser of the SplitMix64 generator (Steele, Lea, Flood 2014).
+ * Normal deviates use the Box-Muller transform on the two 32-bit halves of word(i / 2):
+ * element i takes the cosine branch when i is even and the sine branch when i is odd.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stddef.h>
+
+static inline uint64_t mix(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ULL;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+
+static inline uint64_t stream_key(uint64_t seed, uint64_t stream_id) { return mix(seed ^ mix(stream_id)); }
+static inline uint64_t word(uint64_t key, uint64_t c) { return mix(key + c * 0x9E3779B97F4A7C15ULL); }
+
+static inline double normal_at(uint64_t key, uint64_t i) {
+  uint64_t r = word(key, i >> 1);
+  double u1 = ((double)(r >> 32) + 0.5) * (1.0 / 4294967296.0);
+  double u2 = ((double)(r & 0xFFFFFFFFULL) + 0.5) * (1.0 / 4294967296.0);
+  double rad = sqrt(-2.0 * log(u1));
+  double ang = 6.283185307179586476925286766559 * u2;
+  return (i & 1) ? rad * sin(ang) : rad * cos(ang);
+}
+
+/* round-to-nearest-even fp32 -> bf16 bit pattern (inputs are finite) */
+static inline uint16_t f32_to_bf16_bits(float f) {
+  union { float f; uint32_t u; } v; v.f = f;
+  uint32_t lsb = (v.u >> 16) & 1u;
+  return (uint16_t)((v.u + 0x7FFFu + lsb) >> 16);
+}
+
+/* out[i] = mean + std * N(0,1), i in [0,n), element counter starts at first */
+void wwwsynth_normal_f32(uint64_t seed, uint64_t stream_id, uint64_t first, uint64_t n, double mean, double std, float* out) {
+  uint64_t key = stream_key(seed, stream_id);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i) out[i] = (float)(mean + std * normal_at(key, first + (uint64_t)i));
+}
+
+/* as above, rounded fp32 -> bf16 (nearest even), stored as 16-bit patterns */
+void wwwsynth_normal_bf16(uint64_t seed, uint64_t stream_id, uint64_t first, uint64_t n, double mean, double std, uint16_t* out) {
+  uint64_t key = stream_key(seed, stream_id);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i)
+    out[i] = f32_to_bf16_bits((float)(mean + std * normal_at(key, first + (uint64_t)i)));
+}
+
+/* the bare mixing function, exported so that tests can check it against SplitMix64's published outputs */
+uint64_t wwwsynth_mix(uint64_t z) { return mix(z); }
+
+/* raw 64-bit words of the stream */
+void wwwsynth_words(uint64_t seed, uint64_t stream_id, uint64_t first, uint64_t n, uint64_t* out) {
+  uint64_t key = stream_key(seed, stream_id);
+  for (uint64_t i = 0; i < n; ++i) out[i] = word(key, first + i);
+}
+
+/* integers uniform on [0, bound): high 32 bits of word scaled by bound (bound < 2^31) */
+void wwwsynth_uniform_i32(uint64_t seed, uint64_t stream_id, uint64_t first, uint64_t n, uint32_t bound, int32_t* out) {
+  uint64_t key = stream_key(seed, stream_id);
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i)
+    out[i] = (int32_t)(((word(key, first + (uint64_t)i) >> 32) * (uint64_t)bound) >> 32);
+}
