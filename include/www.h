@@ -1,0 +1,136 @@
+/* www.h -- C ABI of the MI355X (gfx950) inference library behind a WWW.Serve provider node.
+ *
+ * In the paper a provider's Model Manager hands each dispatched request to a local serving backend
+ * and only sees its completions and load figures (Sec. 3.2 "Model Manager"; App. A.1 "Local
+ * execution"; App. B).  Executors generate greedily (App. C, temperature 0); a duel runs the same
+ * request on two executors and each judge reads both answers in one pass (Sec. 4.2).  This library
+ * is that backend's compute path: batched decoder inference with a paged KV cache.
+ *
+ *   www_model_load   bind a weight blob, a KV pool and a workspace; repack weights for the matrix cores
+ *   www_prefill      run new prompt tokens (whole prompts or chunks) and fill the KV cache
+ *   www_decode_step  append one token per sequence and return next-token logits
+ *
+ * The function computed is the standard pre-norm decoder (RMSNorm, grouped-query attention with
+ * rotary embedding on half-split pairs, SwiGLU, untied output head, greedy argmax with the lowest
+ * index winning ties); the paper itself gives no model equations.
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; the library borrows it and
+ *    never allocates or frees device memory.  Pointers without the suffix are host memory.
+ *  - `hip_stream` is a hipStream_t passed as void*; all work of a call is enqueued on it and the
+ *    call returns without synchronising (except www_model_load, which waits for its own packing).
+ *    Calls on one model must not overlap: they share the model's workspace.
+ *  - Return value: 0 on success, a negative WWW_E_* code otherwise; www_last_error() then gives
+ *    a message for the calling thread.  Argument checks run on the host before anything is
+ *    launched.  Contents of device arrays (token ids, block ids, lengths) are NOT checked: the
+ *    caller guarantees  0 <= token < vocab,  0 <= block id < num_kv_blocks for every block a
+ *    sequence uses, distinct blocks for distinct (sequence, position/16), and
+ *    q_lens <= seq_lens <= max_blocks_per_seq * 16.
+ *
+ * Weight blob (source format, device memory, may be released after www_model_load returns).
+ * Tensors in this order, each starting on a 256-byte boundary, every matrix row-major
+ * [out_features][in_features] in `weight_dtype`, gains in fp32:
+ *     embed[vocab][d]
+ *     per layer: attn_norm[d], wqkv[(Hq+2Hkv)*hd][d] (q heads, then k heads, then v heads),
+ *                wo[d][Hq*hd], ffn_norm[d], wgu[2F][d] (gate rows, then up rows), wd[d][F]
+ *     final_norm[d], lm_head[vocab][d]
+ *
+ * KV pool (device, caller-owned, contents opaque to the caller): 2 bytes per element, num_kv_blocks blocks of
+ * kv_block_size = 16 token slots.  Logical position p of sequence b lives in block
+ * block_table[b][p / 16], slot p % 16.
+ */
+#ifndef WWW_H
+#define WWW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WWW_ABI_VERSION 1u
+
+#define WWW_OK 0
+#define WWW_E_INVALID_ARG (-1)  /* null pointer, negative count, misaligned buffer */
+#define WWW_E_BAD_CONFIG (-2)   /* unsupported shape (see www_config) */
+#define WWW_E_ABI_MISMATCH (-3) /* config.abi_version != WWW_ABI_VERSION */
+#define WWW_E_CAPACITY (-4)     /* batch > max_batch, tokens > max_prefill_tokens, ... */
+#define WWW_E_HIP (-5)          /* a HIP runtime call failed; message holds hipGetErrorString */
+
+#define WWW_DTYPE_F32 0u  /* weights given in fp32: kept as two fp16 terms (hi + lo) */
+#define WWW_DTYPE_BF16 1u /* weights given in bf16: converted to fp16 (exact for |w| >= 2^-17) */
+
+typedef struct www_model www_model; /* opaque handle */
+
+/* Model shape and capacities.  Supported: head_dim in {64, 128}; d_model % 32 == 0; ffn_dim % 16 == 0;
+ * vocab % 16 == 0; n_q_heads % n_kv_heads == 0 with a group size <= 16; kv_block_size == 16. */
+typedef struct {
+  uint32_t abi_version; /* WWW_ABI_VERSION */
+  uint32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+  float rms_eps, rope_theta;
+  uint32_t kv_block_size;      /* 16 */
+  uint32_t weight_dtype;       /* WWW_DTYPE_* of the source blob */
+  uint32_t max_batch;          /* most sequences in one call */
+  uint32_t max_blocks_per_seq; /* row length of block tables; longest sequence = 16 * this */
+  uint32_t max_prefill_tokens; /* most new tokens in one www_prefill call (sum of q_lens) */
+  uint32_t reserved;           /* 0 */
+  uint64_t num_kv_blocks;      /* blocks in the KV pool */
+} www_config;
+
+/* Sizes in bytes of the three caller-provided device buffers for this configuration.
+ * Any out pointer may be NULL.  Errors: INVALID_ARG, ABI_MISMATCH, BAD_CONFIG. */
+int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_bytes, uint64_t* kv_pool_bytes, uint64_t* workspace_bytes);
+
+/* Creates a model.  Repacks the blob into the workspace (matrix-core fragment order), builds the
+ * rotary table, zeroes the workspace's counters and waits for that work on `hip_stream`.
+ * weights_dev is only read during this call.  kv_pool_dev and workspace_dev (256-byte aligned, sizes
+ * from www_query_sizes) stay borrowed until www_model_free.  The KV pool is not cleared.
+ * Errors: INVALID_ARG, ABI_MISMATCH, BAD_CONFIG, HIP. */
+int www_model_load(const www_config* cfg, const void* weights_dev, void* kv_pool_dev, void* workspace_dev, void* hip_stream,
+                   www_model** out);
+
+/* Prefill: processes q_lens[b] new tokens of each of `batch` sequences and writes their keys and
+ * values into the KV pool.  Sequence b's new tokens occupy positions seq_lens[b]-q_lens[b] ..
+ * seq_lens[b]-1; earlier positions must already be cached (chunked prefill) and are attended to.
+ *   tokens_dev       int32 [total_q_tokens], sequences packed back to back
+ *   q_lens_dev       int32 [batch], each >= 1
+ *   seq_lens_dev     int32 [batch], length after this call
+ *   block_table_dev  int32 [batch][max_blocks_per_seq]; unused entries are ignored
+ *   logits_dev       fp32 [batch][vocab], logits at the LAST new position of each sequence; may be NULL
+ *   next_tokens_dev  int32 [batch], argmax of those logits; may be NULL
+ * Errors: INVALID_ARG, CAPACITY (batch > max_batch, total_q_tokens > max_prefill_tokens), HIP. */
+int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
+                const int32_t* block_table_dev, int32_t batch, int32_t total_q_tokens, float* logits_dev, int32_t* next_tokens_dev,
+                void* hip_stream);
+
+/* One decode step: sequence b appends last_tokens[b] at position seq_lens[b]-1 (so seq_lens is the
+ * length AFTER the append) and attends to positions 0 .. seq_lens[b]-1.
+ *   last_tokens_dev  int32 [batch];  seq_lens_dev int32 [batch];  block_table_dev as above
+ *   logits_dev       fp32 [batch][vocab]; may be NULL
+ *   next_tokens_dev  int32 [batch] greedy next token; may be NULL
+ * The step is replayed from a captured HIP graph keyed on (batch, pointers, stream); lengths, tables
+ * and tokens are read from device memory at run time, so the same arrays can be updated in place
+ * between steps.  Errors: INVALID_ARG, CAPACITY, HIP. */
+int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
+                    int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream);
+
+/* Releases the handle and its HIP graphs.  Device buffers remain the caller's.  NULL is allowed. */
+void www_model_free(www_model* m);
+
+/* Message of the last error on this thread ("" if none); storage is thread-local and static. */
+const char* www_last_error(void);
+
+/* Test hook: physical token slot of (block-table row, position), computed on the device by the same
+ * routine the cache-writing kernels use.  table_row_dev int32 [n_blocks]; positions_dev int32 [n];
+ * slots_dev int64 [n] receives block * 16 + position % 16.  Errors: INVALID_ARG, HIP. */
+int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream);
+
+/* Test hook: copies an internal fp32 buffer of the last call to host memory after synchronising the
+ * stream.  which: 0 = residual stream of the decode path [batch][d_model].
+ * Errors: INVALID_ARG, HIP. */
+int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WWW_H */

@@ -1,0 +1,146 @@
+"""ctypes binding of the C ABI declared in include/www.h.
+
+Argument marshalling only: every function takes torch CUDA tensors (used purely as device memory)
+and passes their raw pointers on; every step of the computation runs in the HIP kernels of
+libwww.so.  There is no CPU fallback: importing this module fails if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwww.so")
+
+ABI_VERSION = 1
+E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP = -1, -2, -3, -4, -5
+EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_model_free", "www_last_error",
+           "www_debug_slots", "www_debug_read")
+
+
+class WwwConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("abi_version", "n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab")] + \
+               [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)] + \
+               [(n, ctypes.c_uint32) for n in ("kv_block_size", "weight_dtype", "max_batch", "max_blocks_per_seq",
+                                               "max_prefill_tokens", "reserved")] + \
+               [("num_kv_blocks", ctypes.c_uint64)]
+
+
+class WwwError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"www error {code}: {msg}")
+        self.code = code
+
+
+def _load_library():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2603_20661_amd.build)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, u64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64)
+    cfgp = ctypes.POINTER(WwwConfig)
+    L.www_query_sizes.argtypes = [cfgp, u64p, u64p, u64p]
+    L.www_model_load.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+    L.www_prefill.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+    L.www_decode_step.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+    L.www_model_free.argtypes = [vp]
+    L.www_model_free.restype = None
+    L.www_last_error.argtypes = []
+    L.www_last_error.restype = ctypes.c_char_p
+    L.www_debug_slots.argtypes = [vp, vp, i32, vp, vp]
+    L.www_debug_read.argtypes = [vp, i32, vp, ctypes.c_uint64, vp]
+    for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read"):
+        getattr(L, name).restype = ctypes.c_int
+    return L
+
+
+lib = _load_library()
+
+
+def _check(rc):
+    if rc != 0:
+        raise WwwError(rc, lib.www_last_error().decode())
+
+
+def make_config(shape, max_batch, max_blocks_per_seq, max_prefill_tokens, num_kv_blocks) -> WwwConfig:
+    """shape: object with the model-shape attribute names (n_layers, d_model, ...)."""
+    return WwwConfig(ABI_VERSION, shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     shape.ffn_dim, shape.vocab, shape.rms_eps, shape.rope_theta, shape.kv_block_size, shape.weight_dtype,
+                     max_batch, max_blocks_per_seq, max_prefill_tokens, 0, num_kv_blocks)
+
+
+def www_query_sizes(cfg: WwwConfig):
+    """-> (weight_blob_bytes, kv_pool_bytes, workspace_bytes)"""
+    a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib.www_query_sizes(ctypes.byref(cfg), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+
+
+class Model:
+    """Owns the device buffers (torch allocations) the library borrows, and the opaque handle."""
+
+    def __init__(self, cfg: WwwConfig, blob_dev: torch.Tensor, stream=None, kv_fill=None):
+        wbytes, kvbytes, wsbytes = www_query_sizes(cfg)
+        assert blob_dev.dtype == torch.uint8 and blob_dev.numel() == wbytes, (blob_dev.numel(), wbytes)
+        self.cfg = cfg
+        self.kv_pool = torch.empty(kvbytes, dtype=torch.uint8, device=blob_dev.device)
+        if kv_fill is not None:
+            self.kv_pool.view(torch.int16).fill_(kv_fill)
+        self.workspace = torch.empty(wsbytes, dtype=torch.uint8, device=blob_dev.device)
+        h = ctypes.c_void_p()
+        _check(lib.www_model_load(ctypes.byref(cfg), _ptr(blob_dev), _ptr(self.kv_pool), _ptr(self.workspace), _stream(stream),
+                                  ctypes.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.www_model_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+
+def www_prefill(model: Model, tokens, q_lens, seq_lens, block_table, logits=None, next_tokens=None, stream=None):
+    i32 = torch.int32
+    batch, total = q_lens.numel(), tokens.numel()
+    if logits is not None:
+        assert logits.shape == (batch, model.cfg.vocab)
+    _check(lib.www_prefill(model._h, _ptr(tokens, i32), _ptr(q_lens, i32), _ptr(seq_lens, i32), _ptr(block_table, i32), batch, total,
+                           _ptr(logits, torch.float32), _ptr(next_tokens, i32), _stream(stream)))
+
+
+def www_decode_step(model: Model, last_tokens, seq_lens, block_table, logits=None, next_tokens=None, stream=None):
+    i32 = torch.int32
+    batch = last_tokens.numel()
+    if logits is not None:
+        assert logits.shape == (batch, model.cfg.vocab)
+    _check(lib.www_decode_step(model._h, _ptr(last_tokens, i32), _ptr(seq_lens, i32), _ptr(block_table, i32), batch,
+                               _ptr(logits, torch.float32), _ptr(next_tokens, i32), _stream(stream)))
+
+
+def www_debug_slots(table_row, positions, stream=None):
+    out = torch.empty(positions.numel(), dtype=torch.int64, device=positions.device)
+    _check(lib.www_debug_slots(_ptr(table_row, torch.int32), _ptr(positions, torch.int32), positions.numel(), _ptr(out), _stream(stream)))
+    return out
+
+
+def www_debug_read(model: Model, which: int, n_floats: int, stream=None):
+    out = torch.empty(n_floats, dtype=torch.float32)
+    _check(lib.www_debug_read(model._h, which, out.data_ptr(), n_floats, _stream(stream)))
+    return out

@@ -1,0 +1,350 @@
+// C ABI (include/www.h): argument checks, workspace plan, weight packing at load, prefill,
+// graph-captured decode step.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+int decode_gemm_ksplit(int NRG, int KB, int MT);
+int decode_MT(int batch);
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+#define HIP_TRY(x)                                                       \
+  do {                                                                   \
+    hipError_t e_ = (x);                                                 \
+    if (e_ != hipSuccess) {                                              \
+      set_error("%s failed: %s", #x, hipGetErrorString(e_));             \
+      return WWW_E_HIP;                                                  \
+    }                                                                    \
+  } while (0)
+
+static int check_config(const www_config* c) {
+  if (!c) { set_error("config is NULL"); return WWW_E_INVALID_ARG; }
+  if (c->abi_version != WWW_ABI_VERSION) { set_error("abi_version %u, library has %u", c->abi_version, WWW_ABI_VERSION); return WWW_E_ABI_MISMATCH; }
+  const char* why = nullptr;
+  if (c->n_layers == 0 || c->d_model == 0 || c->vocab == 0 || c->ffn_dim == 0 || c->n_kv_heads == 0) why = "zero dimension";
+  else if (c->head_dim != 64 && c->head_dim != 128) why = "head_dim must be 64 or 128";
+  else if (c->d_model % 128 || c->d_model > 128 * SSQ_TILES) why = "d_model must be a multiple of 128, at most 8192";
+  else if (c->ffn_dim % 16) why = "ffn_dim must be a multiple of 16";
+  else if (c->vocab % 16) why = "vocab must be a multiple of 16";
+  else if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 16) why = "n_q_heads must be a multiple of n_kv_heads, group size <= 16";
+  else if (c->kv_block_size != KV_BS) why = "kv_block_size must be 16";
+  else if (c->weight_dtype > 1) why = "weight_dtype must be 0 (fp32) or 1 (bf16)";
+  else if (c->max_batch == 0 || c->max_batch > 1024) why = "max_batch must be in 1..1024";
+  else if (c->max_blocks_per_seq == 0 || c->num_kv_blocks == 0) why = "empty KV pool";
+  else if (c->num_kv_blocks > 0x7fffffffull) why = "num_kv_blocks must fit int32";
+  else if (c->max_prefill_tokens == 0) why = "max_prefill_tokens must be positive";
+  else if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) why = "bad rms_eps / rope_theta";
+  else if (c->reserved != 0) why = "reserved must be 0";
+  if (why) { set_error("unsupported configuration: %s", why); return WWW_E_BAD_CONFIG; }
+  return WWW_OK;
+}
+
+static uint64_t align256(uint64_t n) { return (n + 255) / 256 * 256; }
+
+// byte offsets of everything inside the workspace
+struct Plan {
+  uint64_t total;
+  uint64_t embed, final_norm, lm_head, lm_head_lo, rope;
+  std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
+  uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
+  uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok;
+  uint64_t hp, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
+  int attn_kps, attn_splits;
+};
+
+struct Dims {
+  int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, maxB, MTmax, maxT, max_pos;
+  bool wsplit;
+};
+
+static Dims dims_of(const www_config* c) {
+  Dims s;
+  s.L = c->n_layers; s.d = c->d_model; s.Hq = c->n_q_heads; s.Hkv = c->n_kv_heads; s.hd = c->head_dim; s.G = s.Hq / s.Hkv;
+  s.F = c->ffn_dim; s.Fp = (s.F + 31) / 32 * 32; s.V = c->vocab;
+  s.QD = s.Hq * s.hd; s.KD = s.Hkv * s.hd; s.QKVN = s.QD + 2 * s.KD;
+  s.maxB = c->max_batch; s.MTmax = decode_MT(s.maxB); s.maxT = c->max_prefill_tokens;
+  s.max_pos = c->max_blocks_per_seq * KV_BS;
+  s.wsplit = c->weight_dtype == WWW_DTYPE_F32;
+  return s;
+}
+
+static void make_plan(const www_config* c, Plan& p) {
+  const Dims s = dims_of(c);
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += align256(bytes); return o; };
+  const uint64_t wb = s.wsplit ? 4 : 2;
+  p.embed = take((uint64_t)s.V * s.d * wb);
+  p.final_norm = take((uint64_t)s.d * 4);
+  p.lm_head = take((uint64_t)s.V * s.d * 2);
+  p.lm_head_lo = s.wsplit ? take((uint64_t)s.V * s.d * 2) : 0;
+  p.rope = take((uint64_t)s.max_pos * (s.hd / 2) * 8);
+  for (int l = 0; l < s.L; ++l) {
+    p.attn_norm.push_back(take((uint64_t)s.d * 4));
+    p.ffn_norm.push_back(take((uint64_t)s.d * 4));
+    p.wqkv.push_back(take((uint64_t)s.QKVN * s.d * 2));
+    p.wqkv_lo.push_back(s.wsplit ? take((uint64_t)s.QKVN * s.d * 2) : 0);
+    p.wo.push_back(take((uint64_t)s.d * s.QD * 2));
+    p.wo_lo.push_back(s.wsplit ? take((uint64_t)s.d * s.QD * 2) : 0);
+    p.wgu.push_back(take((uint64_t)2 * s.F * s.d * 2));
+    p.wgu_lo.push_back(s.wsplit ? take((uint64_t)2 * s.F * s.d * 2) : 0);
+    p.wd.push_back(take((uint64_t)s.d * s.Fp * 2));
+    p.wd_lo.push_back(s.wsplit ? take((uint64_t)s.d * s.Fp * 2) : 0);
+  }
+  p.zero_begin = off;
+  const uint64_t Mpad = (uint64_t)s.MTmax * 16;
+  p.counters = take((65536 + (uint64_t)s.maxB * s.Hkv) * 4);
+  p.h = take(Mpad * s.d * 4);
+  p.ssq = take((uint64_t)SSQ_TILES * s.maxB * 4);
+  p.q = take(Mpad * s.QD * 4);
+  p.xq = take(Mpad * s.d * 4);
+  p.xo = take(Mpad * s.QD * 4);
+  p.xa = take(Mpad * s.Fp * 4);
+  uint64_t part = 0;
+  {
+    const int N[5] = {s.QKVN, s.d, 2 * s.F, s.d, s.V};
+    const int K[5] = {s.d, s.QD, s.d, s.Fp, s.d};
+    for (int i = 0; i < 5; ++i)
+      for (int mt = 1; mt <= s.MTmax; mt = mt < 4 ? mt * 2 : mt + 4) {  // every token-group count a batch can produce
+        uint64_t ks = decode_gemm_ksplit(N[i] / 16, K[i] / 32, mt);
+        uint64_t bytes = ks * mt * 16 * N[i] * 4;
+        if (ks > 1 && bytes > part) part = bytes;
+      }
+  }
+  p.partial = take(part ? part : 256);
+  p.attn_kps = 256;
+  p.attn_splits = (s.max_pos + p.attn_kps - 1) / p.attn_kps;
+  p.attn_part = take((uint64_t)s.maxB * s.Hkv * p.attn_splits * s.G * (s.hd + 4) * 4);
+  p.logits = take((uint64_t)s.maxB * s.V * 4);
+  p.last_tok = take((uint64_t)s.maxB * 4);
+  p.hp = take((uint64_t)s.maxT * s.d * 4);
+  p.xn = take((uint64_t)s.maxT * s.d * 2);
+  p.qp = take((uint64_t)s.maxT * s.QD * 2);
+  p.op = take((uint64_t)s.maxT * s.QD * 2);
+  p.ap = take((uint64_t)s.maxT * s.Fp * 2);
+  p.row_seq = take((uint64_t)s.maxT * 4);
+  p.row_pos = take((uint64_t)s.maxT * 4);
+  const uint64_t max_tiles = (uint64_t)s.maxT / 64 + s.maxB + 1;
+  p.tile_seq = take(max_tiles * 4);
+  p.tile_q0 = take(max_tiles * 4);
+  p.meta = take((16 + 2 * ((uint64_t)s.maxB + 1)) * 4);
+  p.zero_end = off;
+  p.total = off;
+}
+
+static uint64_t blob_bytes(const www_config* c) {
+  const Dims s = dims_of(c);
+  const uint64_t wb = s.wsplit ? 4 : 2;
+  uint64_t off = align256((uint64_t)s.V * s.d * wb);
+  for (int l = 0; l < s.L; ++l)
+    off += align256((uint64_t)s.d * 4) * 2 + align256((uint64_t)s.QKVN * s.d * wb) + align256((uint64_t)s.d * s.QD * wb) +
+           align256((uint64_t)2 * s.F * s.d * wb) + align256((uint64_t)s.d * s.F * wb);
+  off += align256((uint64_t)s.d * 4) + align256((uint64_t)s.V * s.d * wb);
+  return off;
+}
+
+extern "C" int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_bytes, uint64_t* kv_pool_bytes, uint64_t* workspace_bytes) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  const Dims s = dims_of(cfg);
+  Plan p;
+  make_plan(cfg, p);
+  if (weight_blob_bytes) *weight_blob_bytes = blob_bytes(cfg);
+  if (kv_pool_bytes) *kv_pool_bytes = (uint64_t)cfg->num_kv_blocks * s.L * 2 * s.Hkv * KV_BS * s.hd * 2;
+  if (workspace_bytes) *workspace_bytes = p.total;
+  return WWW_OK;
+}
+
+extern "C" int www_model_load(const www_config* cfg, const void* weights_dev, void* kv_pool_dev, void* workspace_dev, void* hip_stream,
+                              www_model** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!weights_dev || !kv_pool_dev || !workspace_dev || !out) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  if (((uintptr_t)weights_dev | (uintptr_t)kv_pool_dev | (uintptr_t)workspace_dev) & 255) { set_error("device buffers must be 256-byte aligned"); return WWW_E_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Dims s = dims_of(cfg);
+  Plan p;
+  make_plan(cfg, p);
+  char* ws = (char*)workspace_dev;
+  const char* blob = (const char*)weights_dev;
+  const uint64_t wb = s.wsplit ? 4 : 2;
+  const int dt = (int)cfg->weight_dtype;
+
+  HIP_TRY(hipMemsetAsync(ws + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
+
+  www_model* m = new www_model();
+  memset(m, 0, sizeof(*m));
+  m->cfg = *cfg;
+  m->L = s.L; m->d = s.d; m->Hq = s.Hq; m->Hkv = s.Hkv; m->hd = s.hd; m->G = s.G; m->F = s.F; m->Fp = s.Fp; m->V = s.V;
+  m->QKVN = s.QKVN; m->QD = s.QD; m->KD = s.KD; m->max_pos = s.max_pos; m->maxB = s.maxB; m->MTmax = s.MTmax; m->maxT = s.maxT;
+  m->wsplit = s.wsplit;
+  m->layers = new LayerW[s.L];
+  m->graphs = new GraphEntry[16];
+  m->n_graphs = 0;
+  const char* env = getenv("WWW_NO_GRAPH");
+  m->use_graph = !(env && env[0] == '1');
+
+  auto fail = [&](int code) { delete[] m->layers; delete[] m->graphs; delete m; return code; };
+#define LOAD_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { set_error("%s failed: %s", #x, hipGetErrorString(e_)); return fail(WWW_E_HIP); } } while (0)
+
+  uint64_t src = 0;
+  auto pack = [&](int N, int K, int mode, uint64_t hi, uint64_t lo) {
+    int KB = (K + 31) / 32;
+    int r = launch_pack_matrix(blob + src, dt, N, K, KB, mode, s.hd, (s.Hq + s.Hkv) * s.hd, s.F, (uint16_t*)(ws + hi), s.wsplit ? (uint16_t*)(ws + lo) : nullptr, st);
+    src += align256((uint64_t)N * K * wb);
+    return r;
+  };
+  // embed
+  LOAD_TRY(hipMemcpyAsync(ws + p.embed, blob + src, (uint64_t)s.V * s.d * wb, hipMemcpyDeviceToDevice, st));
+  src += align256((uint64_t)s.V * s.d * wb);
+  for (int l = 0; l < s.L; ++l) {
+    LayerW& w = m->layers[l];
+    LOAD_TRY(hipMemcpyAsync(ws + p.attn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
+    src += align256((uint64_t)s.d * 4);
+    if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    LOAD_TRY(hipMemcpyAsync(ws + p.ffn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
+    src += align256((uint64_t)s.d * 4);
+    if (pack(2 * s.F, s.d, 2, p.wgu[l], p.wgu_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.F, 0, p.wd[l], p.wd_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    w.wqkv = (const uint16_t*)(ws + p.wqkv[l]); w.wo = (const uint16_t*)(ws + p.wo[l]);
+    w.wgu = (const uint16_t*)(ws + p.wgu[l]); w.wd = (const uint16_t*)(ws + p.wd[l]);
+    w.wqkv_lo = s.wsplit ? (const uint16_t*)(ws + p.wqkv_lo[l]) : nullptr; w.wo_lo = s.wsplit ? (const uint16_t*)(ws + p.wo_lo[l]) : nullptr;
+    w.wgu_lo = s.wsplit ? (const uint16_t*)(ws + p.wgu_lo[l]) : nullptr; w.wd_lo = s.wsplit ? (const uint16_t*)(ws + p.wd_lo[l]) : nullptr;
+    w.attn_norm = (const float*)(ws + p.attn_norm[l]); w.ffn_norm = (const float*)(ws + p.ffn_norm[l]);
+  }
+  LOAD_TRY(hipMemcpyAsync(ws + p.final_norm, blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
+  src += align256((uint64_t)s.d * 4);
+  if (pack(s.V, s.d, 0, p.lm_head, p.lm_head_lo)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+
+  // rotary table: angle = pos * theta^(-2i/hd) evaluated in double, stored as (cos, sin) in fp32
+  {
+    std::vector<float> tab((size_t)s.max_pos * (s.hd / 2) * 2);
+    for (int i = 0; i < s.hd / 2; ++i) {
+      double freq = pow((double)cfg->rope_theta, -2.0 * i / s.hd);
+      for (int pos = 0; pos < s.max_pos; ++pos) {
+        double a = pos * freq;
+        tab[((size_t)pos * (s.hd / 2) + i) * 2] = (float)cos(a);
+        tab[((size_t)pos * (s.hd / 2) + i) * 2 + 1] = (float)sin(a);
+      }
+    }
+    LOAD_TRY(hipMemcpyAsync(ws + p.rope, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, st));
+    LOAD_TRY(hipStreamSynchronize(st));  // tab is about to go out of scope; also fences the packing kernels
+  }
+#undef LOAD_TRY
+
+  m->embed = ws + p.embed;
+  m->lm_head = (const uint16_t*)(ws + p.lm_head);
+  m->lm_head_lo = s.wsplit ? (const uint16_t*)(ws + p.lm_head_lo) : nullptr;
+  m->final_norm = (const float*)(ws + p.final_norm);
+  m->rope = (const float2*)(ws + p.rope);
+  m->kv = (uint16_t*)kv_pool_dev;
+  m->kv_plane = (int64_t)cfg->num_kv_blocks * s.Hkv * KV_BS * s.hd;
+  m->h = (float*)(ws + p.h); m->ssq = (float*)(ws + p.ssq); m->q = (float*)(ws + p.q);
+  m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
+  m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
+  m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
+  m->hp = (float*)(ws + p.hp); m->xn = (uint16_t*)(ws + p.xn); m->qp = (uint16_t*)(ws + p.qp); m->op = (uint16_t*)(ws + p.op); m->ap = (uint16_t*)(ws + p.ap);
+  m->row_seq = (int*)(ws + p.row_seq); m->row_pos = (int*)(ws + p.row_pos); m->tile_seq = (int*)(ws + p.tile_seq);
+  m->tile_q0 = (int*)(ws + p.tile_q0); m->meta = (int*)(ws + p.meta);
+  m->attn_kps = p.attn_kps; m->attn_splits = p.attn_splits;
+  *out = m;
+  return WWW_OK;
+}
+
+extern "C" int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
+                           const int32_t* block_table_dev, int32_t batch, int32_t total_q_tokens, float* logits_dev,
+                           int32_t* next_tokens_dev, void* hip_stream) {
+  if (!m || !tokens_dev || !q_lens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  if (batch < 0 || total_q_tokens < 0 || total_q_tokens < batch) { set_error("bad batch / total_q_tokens"); return WWW_E_INVALID_ARG; }
+  if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
+  if (total_q_tokens > m->maxT) { set_error("total_q_tokens %d exceeds max_prefill_tokens %d", total_q_tokens, m->maxT); return WWW_E_CAPACITY; }
+  if (batch == 0) return WWW_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int rc = run_prefill(m, tokens_dev, q_lens_dev, seq_lens_dev, block_table_dev, batch, total_q_tokens, st);
+  if (rc) return rc;
+  // the last new position of every sequence goes through the decode path (hi/lo activations), which also yields the logits
+  return run_decode(m, m->last_tok, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
+}
+
+extern "C" int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
+                               int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream) {
+  if (!m || !last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  if (batch < 0) { set_error("negative batch"); return WWW_E_INVALID_ARG; }
+  if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
+  if (batch == 0) return WWW_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!m->use_graph || st == nullptr)  // the legacy default stream cannot be captured
+    return run_decode(m, last_tokens_dev, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
+
+  for (int i = 0; i < m->n_graphs; ++i) {
+    GraphEntry& g = m->graphs[i];
+    if (g.batch == batch && g.tok == last_tokens_dev && g.lens == seq_lens_dev && g.table == block_table_dev && g.logits == logits_dev &&
+        g.next == next_tokens_dev && g.stream == st) {
+      HIP_TRY(hipGraphLaunch(g.exec, st));
+      return WWW_OK;
+    }
+  }
+  // capture one step; pointers and grid sizes are frozen, lengths / tables / tokens are read from device memory at replay
+  hipGraph_t graph = nullptr;
+  HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+  int rc = run_decode(m, last_tokens_dev, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
+  hipError_t ec = hipStreamEndCapture(st, &graph);
+  if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+  if (ec != hipSuccess) { set_error("hipStreamEndCapture failed: %s", hipGetErrorString(ec)); return WWW_E_HIP; }
+  hipGraphExec_t exec = nullptr;
+  hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (ei != hipSuccess) { set_error("hipGraphInstantiate failed: %s", hipGetErrorString(ei)); return WWW_E_HIP; }
+  if (m->n_graphs == 16) {  // evict the oldest
+    (void)hipGraphExecDestroy(m->graphs[0].exec);
+    memmove(&m->graphs[0], &m->graphs[1], 15 * sizeof(GraphEntry));
+    m->n_graphs = 15;
+  }
+  GraphEntry& g = m->graphs[m->n_graphs++];
+  g.batch = batch; g.tok = last_tokens_dev; g.lens = seq_lens_dev; g.table = block_table_dev; g.logits = logits_dev; g.next = next_tokens_dev;
+  g.stream = st; g.exec = exec;
+  HIP_TRY(hipGraphLaunch(exec, st));
+  return WWW_OK;
+}
+
+extern "C" void www_model_free(www_model* m) {
+  if (!m) return;
+  for (int i = 0; i < m->n_graphs; ++i) (void)hipGraphExecDestroy(m->graphs[i].exec);
+  delete[] m->graphs;
+  delete[] m->layers;
+  delete m;
+}
+
+extern "C" const char* www_last_error(void) { return g_err; }
+
+extern "C" int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream) {
+  if (!table_row_dev || !positions_dev || !slots_dev || n < 0) { set_error("bad argument"); return WWW_E_INVALID_ARG; }
+  if (launch_debug_slots(table_row_dev, positions_dev, n, slots_dev, (hipStream_t)hip_stream)) { set_error("launch failed"); return WWW_E_HIP; }
+  return WWW_OK;
+}
+
+extern "C" int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream) {
+  if (!m || !dst_host) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  const float* src = nullptr;
+  uint64_t cap = 0;
+  if (which == 0) { src = m->h; cap = (uint64_t)m->MTmax * 16 * m->d; }
+  else { set_error("unknown buffer %d", which); return WWW_E_INVALID_ARG; }
+  if (n_floats > cap) { set_error("buffer holds %llu floats", (unsigned long long)cap); return WWW_E_INVALID_ARG; }
+  HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+  HIP_TRY(hipMemcpy(dst_host, src, n_floats * 4, hipMemcpyDeviceToHost));
+  return WWW_OK;
+}

@@ -1,0 +1,132 @@
+// Shared declarations of the gfx950 inference library: vector types, fp16 helpers, the layouts of
+// packed weights / packed activations / KV-cache blocks, and the model handle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/www.h"
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+#define KV_BS 16  // tokens per KV block
+
+// ------------------------------------------------------------------------------------------------
+// Number format.  Every MFMA operand is IEEE fp16, stored as 16-bit patterns (uint16_t).  Weights that
+// arrive in bf16 have 8 significant bits and convert to fp16 exactly for |w| >= 2^-17 (below that the
+// absolute error is at most 2^-25); activations keep 11 significant bits instead of bf16's 8, which
+// is what holds the logit error inside the tolerance; values are clamped to +-65504 on conversion.
+// Where one fp16 is not enough (decode-path activations, fp32 weights) a value is carried as hi + lo.
+//
+// Layouts
+//
+// Packed weight matrix W[N][K] (out x in), K padded with zeros to KB*32:
+//   fragment (rg, kb) = rows rg*16..+15, columns kb*32..+31, 1 KiB, stored lane-major for the
+//   16x16x32 MFMA A operand: lane l holds row rg*16 + l%16, columns kb*32 + (l/16)*8 .. +7.
+//   element offset = ((rg*KB + kb)*64 + l)*8 + e.
+//   Rows may be permuted at pack time (packed row p <-> source row, see pack.hip):
+//     QKV: inside each q and k head, p = 2i -> i, p = 2i+1 -> i + hd/2  (rotary pairs adjacent)
+//     gate/up: row-group 2j = gate rows 16j..16j+15, row-group 2j+1 = up rows 16j..16j+15
+//
+// Packed activations X[M][K] for the decode path, tokens in groups of 16 (MT groups), hi/lo split:
+//   fragment (kb, tb, hl) = tokens tb*16..+15, columns kb*32..+31 as the MFMA B operand:
+//   lane l holds token tb*16 + l%16, columns kb*32 + (l/16)*8 .. +7; x = hi + lo with hi = fp16(x).
+//   element offset = (((kb*MT + tb)*2 + hl)*64 + l)*8 + e.
+//
+// KV pool: [layer][K|V][block][kv head][16 tokens x hd]; inside one (block, head):
+//   K (head-dim in rotary-interleaved order c): offset = ((c/32)*64 + ((c%32)/8)*16 + tok)*8 + c%8
+//        -> fragment c/32 is the A operand of S^T = K Q^T for those 32 dims.
+//   V (head-dim in natural order c):           offset = ((c/16)*64 + (tok/4)*16 + c%16)*4 + tok%4
+//        -> fragment c/16 is the A operand (V^T rows c, 4 keys per lane) of O^T = V^T P^T.
+// ------------------------------------------------------------------------------------------------
+
+__host__ __device__ inline int64_t packed_w_elems(int64_t N, int64_t KB) { return N * KB * 32; }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> fp16 bit pattern, round to nearest even, saturating instead of overflowing to infinity
+__device__ __forceinline__ uint16_t f32_to_f16_sat(float f) {
+  f = fminf(fmaxf(f, -65504.f), 65504.f);
+  return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+__device__ __forceinline__ float f16_bits_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+// x = hi + lo, about 22 significant bits
+__device__ __forceinline__ void split_f16(float x, uint16_t& hi, uint16_t& lo) {
+  hi = f32_to_f16_sat(x);
+  lo = f32_to_f16_sat(x - f16_bits_to_float(hi));
+}
+
+__device__ __forceinline__ int k_cache_offset(int tok, int c) { return ((c >> 5) * 64 + ((c & 31) >> 3) * 16 + tok) * 8 + (c & 7); }
+__device__ __forceinline__ int v_cache_offset(int tok, int c) { return ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3); }
+
+// physical token slot of logical position pos of a sequence with block-table row `row`
+__device__ __forceinline__ int64_t kv_slot(const int32_t* __restrict__ row, int pos) {
+  return (int64_t)row[pos / KV_BS] * KV_BS + (pos % KV_BS);
+}
+
+// ------------------------------------------------------------------------------------------------
+struct LayerW {
+  const uint16_t *wqkv, *wqkv_lo, *wo, *wo_lo, *wgu, *wgu_lo, *wd, *wd_lo;  // packed fp16 (lo planes only for fp32 sources)
+  const float *attn_norm, *ffn_norm;
+};
+
+struct GraphEntry {
+  const void *tok, *lens, *table, *logits, *next;
+  int batch;
+  hipStream_t stream;
+  hipGraphExec_t exec;
+};
+
+struct www_model {
+  www_config cfg;
+  int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, max_pos, maxB, MTmax, maxT;
+  bool wsplit;
+  // weights (inside the workspace)
+  LayerW* layers;  // host array
+  const void* embed;  // [V][d] in the source dtype
+  const uint16_t *lm_head, *lm_head_lo;
+  const float* final_norm;
+  const float2* rope;  // [max_pos][hd/2] (cos, sin)
+  // KV pool
+  uint16_t* kv;  // fp16 bit patterns
+  int64_t kv_plane;  // elements per (layer, K|V) plane = num_blocks * Hkv * 16 * hd
+  // decode-path buffers
+  float* h;        // [maxB][d] residual stream
+  float* ssq;      // [SSQ_TILES][maxB] partial sums of squares of h
+  float* q;        // [maxB][QD]
+  uint16_t* xq;        // packed activations feeding the QKV / gate-up / lm_head GEMMs (K = d)
+  uint16_t* xo;        // packed attention output feeding the O projection (K = QD)
+  uint16_t* xa;        // packed SwiGLU output feeding the down projection (K = Fp)
+  float* partial;  // split-K partial tiles
+  float* attn_part;
+  int* counters;
+  float* logits_buf;  // used when the caller passes no logits buffer
+  int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
+  // prefill-path buffers
+  float* hp;       // [maxT][d]
+  uint16_t* xn;        // [maxT][d] normalised activations
+  uint16_t* qp;    // [maxT][QD] rotated queries, fp16 (interleaved head-dim order)
+  uint16_t* op;        // [maxT][QD] attention output
+  uint16_t* ap;        // [maxT][Fp] SwiGLU output
+  int *row_seq, *row_pos, *tile_seq, *tile_q0, *meta;  // ragged-batch bookkeeping
+  int attn_kps;    // keys per decode-attention split
+  int attn_splits; // grid.x of the decode attention
+  GraphEntry* graphs;
+  int n_graphs;
+  int use_graph;
+};
+
+#define SSQ_TILES 64       // most row tiles of a residual-producing GEMM (d_model / 128)
+#define GEMM_TILE_ROWS 128 // rows of W per workgroup of the skinny GEMM
+#define MAX_KSPLIT 16
+
+// host-side launchers (decode.hip / prefill.hip / pack.hip)
+void set_error(const char* fmt, ...);
+int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int32_t* table, int batch, float* logits, int32_t* next,
+               hipStream_t st);
+int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const int32_t* lens, const int32_t* table, int batch, int T,
+                hipStream_t st);
+int launch_pack_matrix(const void* src, int src_dtype, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F, uint16_t* hi, uint16_t* lo,
+                       hipStream_t st);
+int launch_debug_slots(const int32_t* row, const int32_t* pos, int n, int64_t* out, hipStream_t st);

@@ -1,0 +1,533 @@
+// Prefill path (many new tokens per sequence): ragged-batch bookkeeping, embedding, RMSNorm,
+// LDS-tiled fp16 MFMA GEMM with rotary + KV-cache write / residual / SwiGLU epilogues, and causal
+// paged flash attention over cached prefix + new tokens.  This pass fills the KV cache; the logits
+// of each sequence's last position are produced afterwards by the decode path, which keeps the
+// activations of that one row in hi/lo precision.
+#include "common.h"
+
+#define NEG_INF (-__builtin_inff())
+
+__device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+
+#define ATTN_TQ 64  // query rows per attention workgroup
+
+// ------------------------------------------------------------------------------------------------
+// Ragged batch bookkeeping (one workgroup).  meta[0] = number of attention tiles.
+__global__ __launch_bounds__(1024) void prefill_meta_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ q_lens,
+                                                             const int32_t* __restrict__ seq_lens, int batch, int T,
+                                                             int32_t* __restrict__ row_seq, int32_t* __restrict__ row_pos,
+                                                             int32_t* __restrict__ tile_seq, int32_t* __restrict__ tile_q0,
+                                                             int32_t* __restrict__ meta, int32_t* __restrict__ last_tok,
+                                                             int32_t* __restrict__ cum /* [2*(batch+1)] scratch */) {
+  int32_t* cum_rows = cum;
+  int32_t* cum_tiles = cum + batch + 1;
+  if (threadIdx.x == 0) {
+    int r = 0, tl = 0;
+    for (int b = 0; b < batch; ++b) {
+      cum_rows[b] = r;
+      cum_tiles[b] = tl;
+      r += q_lens[b];
+      tl += (q_lens[b] + ATTN_TQ - 1) / ATTN_TQ;
+    }
+    cum_rows[batch] = r;
+    cum_tiles[batch] = tl;
+    meta[0] = tl;
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < T; r += blockDim.x) {
+    int lo = 0, hi = batch - 1;  // last b with cum_rows[b] <= r
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (cum_rows[mid] <= r) lo = mid; else hi = mid - 1;
+    }
+    row_seq[r] = lo;
+    row_pos[r] = seq_lens[lo] - q_lens[lo] + (r - cum_rows[lo]);
+  }
+  for (int b = threadIdx.x; b < batch; b += blockDim.x) {
+    int nt = cum_tiles[b + 1] - cum_tiles[b];
+    for (int i = 0; i < nt; ++i) {
+      tile_seq[cum_tiles[b] + i] = b;
+      tile_q0[cum_tiles[b] + i] = i * ATTN_TQ;
+    }
+    last_tok[b] = tokens[cum_rows[b + 1] - 1];
+  }
+}
+
+template <typename ET>
+__global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restrict__ tokens, const ET* __restrict__ embed, int d,
+                                                          float* __restrict__ hp) {
+  int64_t r = blockIdx.x;
+  const ET* row = embed + (int64_t)tokens[r] * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    float x;
+    if constexpr (sizeof(ET) == 4) x = (float)row[k];
+    else x = bf16_bits_to_float(((const uint16_t*)row)[k]);
+    hp[r * d + k] = x;
+  }
+}
+
+// xn[r] = fp16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain )
+__global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restrict__ hp, const float* __restrict__ gain, int d, float eps,
+                                                            uint16_t* __restrict__ xn) {
+  int64_t r = blockIdx.x;
+  const float* x = hp + r * d;
+  float local = 0.f;
+  for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
+    float4 v = *reinterpret_cast<const float4*>(x + k);
+    local += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  __shared__ float red[256];
+  red[threadIdx.x] = local;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  float rs = rsqrtf(red[0] / d + eps);
+  for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
+    float4 v = *reinterpret_cast<const float4*>(x + k);
+    float4 g = *reinterpret_cast<const float4*>(gain + k);
+    union { uint16_t s[4]; uint2 v; } o;
+    o.s[0] = f32_to_f16_sat(v.x * rs * g.x);
+    o.s[1] = f32_to_f16_sat(v.y * rs * g.y);
+    o.s[2] = f32_to_f16_sat(v.z * rs * g.z);
+    o.s[3] = f32_to_f16_sat(v.w * rs * g.w);
+    *reinterpret_cast<uint2*>(xn + r * d + k) = o.v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tiled GEMM  Y^T[n][t] = sum_k W[n][k] X[t][k]:  256 weight rows x 256 tokens per workgroup, four
+// wavefronts each owning 128 x 128 as 4 x 4 MFMA 32x32x16 tiles, K in steps of 64 through
+// double-buffered LDS.
+enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
+
+struct PGemmP {
+  const uint4* W;  // packed weights (hi plane)
+  int NRG, KB;
+  const uint16_t* X;  // fp16 activations [T][ldx]
+  int ldx, T;
+  int n_tt, n_rt;  // token tiles, row tiles
+  // QKV epilogue
+  uint16_t* qp;
+  uint16_t *kplane, *vplane;
+  const int32_t *row_seq, *row_pos, *table;
+  int mbs, hd, Hq, Hkv;
+  const float2* rope;
+  // residual epilogue
+  float* hp;
+  int d;
+  // SwiGLU epilogue
+  uint16_t* ap;
+  int Fp;
+};
+
+#define PG_STAGE_UNITS 4096  // 16-byte units per stage: 2048 of W + 2048 of X
+
+template <int EPI>
+__global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
+  extern __shared__ uint4 smem[];  // [2][PG_STAGE_UNITS]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wn = wave >> 1, wt = wave & 1;
+
+  // workgroup -> tile: consecutive ids on one XCD (ids are dealt round-robin to the 8 XCDs) walk
+  // groups of 8 token tiles so that an XCD's L2 sees few distinct weight / activation panels
+  int v = blockIdx.x;
+  const int total = p.n_tt * p.n_rt;
+  if (total % 8 == 0) v = (v % 8) * (total / 8) + v / 8;
+  const int GT = 8;
+  const int per_group = GT * p.n_rt;
+  const int group = v / per_group, first_tt = group * GT;
+  const int gsz = min(GT, p.n_tt - first_tt);
+  const int tt = first_tt + (v % per_group) % gsz;
+  const int rt = (v % per_group) / gsz;
+
+  const int rg_tile = rt * 16;
+  const int t_tile = tt * 256;
+  const int nstages = (p.KB + 1) / 2;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  uint4 sa[8], sb[8];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  auto load_stage = [&](int s) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int u = tid + i * 256;
+      {  // weights: fragment (rgl, kbl), lane u % 64
+        int frag = u >> 6, ln = u & 63;
+        int rgl = frag >> 1, kbl = frag & 1;
+        int rg = min(rg_tile + rgl, p.NRG - 1);
+        int kb = s * 2 + kbl;
+        bool ok = kb < p.KB;
+        uint4 w = p.W[((int64_t)rg * p.KB + (ok ? kb : p.KB - 1)) * 64 + ln];
+        sa[i] = ok ? w : zero4;
+      }
+      {  // activations: token u / 8, 8 columns at (u % 8) * 8
+        int tl = u >> 3, oct = u & 7;
+        int t = min(t_tile + tl, p.T - 1);
+        int k = s * 64 + oct * 8;
+        if (k >= p.KB * 32) k -= 32;  // odd KB: the second half of the last stage meets zero weights
+        sb[i] = *reinterpret_cast<const uint4*>(p.X + (int64_t)t * p.ldx + k);
+      }
+    }
+  };
+  auto store_stage = [&](int buf) {
+    uint4* A = smem + buf * PG_STAGE_UNITS;
+    uint4* B = A + 2048;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int u = tid + i * 256;
+      A[u] = sa[i];
+      int tl = u >> 3, oct = u & 7;
+      // B operand of the 32x32x16 MFMA: block of 32 tokens, 16-column step, lane = (oct & 1) * 32 + token % 32
+      B[(((tl >> 5) * 4 + (oct >> 1)) << 6) + (oct & 1) * 32 + (tl & 31)] = sb[i];
+    }
+  };
+  auto compute = [&](int buf) {
+    const uint4* A = smem + buf * PG_STAGE_UNITS;
+    const uint4* B = A + 2048;
+    const int m = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int k16 = 0; k16 < 4; ++k16) {
+      f16x8 af[4], bfr[4];
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        int rgl = wn * 8 + rb * 2 + (m >> 4);
+        af[rb] = as_f16x8(A[((rgl * 2 + (k16 >> 1)) << 6) + (((k16 & 1) * 2 + hh) << 4) + (m & 15)]);
+      }
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) bfr[tb] = as_f16x8(B[(((wt * 4 + tb) * 4 + k16) << 6) + lane]);
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[rb], bfr[tb], acc[rb][tb], 0, 0, 0);
+    }
+  };
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int s = 0; s < nstages; ++s) {
+    const int buf = s & 1;
+    const bool more = s + 1 < nstages;
+    if (more) load_stage(s + 1);
+    compute(buf);
+    if (more) store_stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // acc[rb][tb][i] = Y^T[row][token]: row = (rg_tile + wn*8 + rb*2)*16 + (i/4)*8 + (lane/32)*4 + i%4, token = t_tile + wt*128 + tb*32 + lane%32
+  const int hsel = lane >> 5;
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) {
+    const int t = t_tile + wt * 128 + tb * 32 + (lane & 31);
+    if (t >= p.T) continue;
+    int pos = 0;
+    int64_t kvbase = 0;
+    int tok = 0;
+    if constexpr (EPI == PEPI_QKV) {
+      pos = p.row_pos[t];
+      int64_t slot = kv_slot(p.table + (int64_t)p.row_seq[t] * p.mbs, pos);
+      kvbase = (slot / KV_BS) * p.Hkv;
+      tok = (int)(slot % KV_BS);
+    }
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+      const int rgb = rg_tile + wn * 8 + rb * 2;  // first of the two row groups of this 32-row block
+      if constexpr (EPI == PEPI_SWIGLU) {
+        if (rgb + 1 >= p.NRG) continue;
+#pragma unroll
+        for (int q4 = 0; q4 < 2; ++q4) {
+          int f0 = (rgb >> 1) * 16 + q4 * 8 + hsel * 4;
+          union { uint16_t s[4]; uint2 v; } o;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float g = acc[rb][tb][q4 * 4 + i], u = acc[rb][tb][(q4 + 2) * 4 + i];
+            o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
+          }
+          *reinterpret_cast<uint2*>(p.ap + (int64_t)t * p.Fp + f0) = o.v;
+        }
+      } else {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int rg = rgb + (q4 >> 1);
+          if (rg >= p.NRG) continue;
+          const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
+          float v4[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i];
+          if constexpr (EPI == PEPI_RESID) {
+            float4* dst = reinterpret_cast<float4*>(p.hp + (int64_t)t * p.d + n0);
+            float4 hv = *dst;
+            *dst = make_float4(hv.x + v4[0], hv.y + v4[1], hv.z + v4[2], hv.w + v4[3]);
+          } else {  // PEPI_QKV
+            const int rot_rows = (p.Hq + p.Hkv) * p.hd;
+            const int head = n0 / p.hd, c0 = n0 % p.hd;
+            if (n0 < rot_rows) {
+#pragma unroll
+              for (int pr = 0; pr < 2; ++pr) {
+                float2 cs = p.rope[(int64_t)pos * (p.hd / 2) + (c0 >> 1) + pr];
+                float a = v4[2 * pr], b = v4[2 * pr + 1];
+                v4[2 * pr] = a * cs.x - b * cs.y;
+                v4[2 * pr + 1] = b * cs.x + a * cs.y;
+              }
+            }
+            union { uint16_t s[4]; uint2 v; } o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(v4[i]);  // q, k, v feed the fp16 attention kernels
+            if (head < p.Hq) {
+              *reinterpret_cast<uint2*>(p.qp + (int64_t)t * (p.Hq * p.hd) + n0) = o.v;
+            } else if (head < p.Hq + p.Hkv) {
+              const int j = head - p.Hq;
+              *reinterpret_cast<uint2*>(p.kplane + (kvbase + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = o.v;
+            } else {
+              const int j = head - p.Hq - p.Hkv;
+              uint16_t* dst = p.vplane + (kvbase + j) * (int64_t)(KV_BS * p.hd);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) dst[v_cache_offset(tok, c0 + i)] = o.s[i];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Causal paged flash attention for new tokens.  One workgroup = 64 consecutive new tokens of one
+// sequence x one kv head (x GH of its query heads); each wavefront owns 16 query positions and keeps
+// S^T = K Q^T / O^T = V^T P^T for its GH heads, so K/V fragments loaded once serve all of them.
+template <int HD, int GH>
+__global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
+                                                            const uint16_t* __restrict__ vplane, const int32_t* __restrict__ q_lens,
+                                                            const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ table,
+                                                            int mbs, int Hq, int Hkv, int G, const int32_t* __restrict__ tile_seq,
+                                                            const int32_t* __restrict__ tile_q0, const int32_t* __restrict__ meta,
+                                                            const int32_t* __restrict__ cum_rows, float scale_log2,
+                                                            uint16_t* __restrict__ op) {
+  constexpr int NKF = HD / 32, NVF = HD / 16;
+  const int tile = blockIdx.x;
+  if (tile >= meta[0]) return;
+  const int j = blockIdx.y;
+  const int h0 = j * G + blockIdx.z * GH;  // first query head handled here
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n = lane & 15, g = lane >> 4;
+  const int b = tile_seq[tile];
+  const int qlen = q_lens[b], ctx = seq_lens[b];
+  const int prefix = ctx - qlen;
+  const int qw0 = tile_q0[tile] + wave * 16;  // first query (index among the new tokens) of this wavefront
+  if (qw0 >= qlen) return;
+  const int nq = min(16, qlen - qw0);
+  const int64_t row0 = (int64_t)cum_rows[b] + qw0;
+  const int my_q = min(n, nq - 1);        // lanes past the end repeat the last query; their output is dropped
+  const int qpos = prefix + qw0 + my_q;   // this lane's query position
+  const int kmax = prefix + qw0 + nq;     // keys 0 .. kmax-1 are visible to some query of the wavefront
+  const int npairs = (kmax + 31) / 32;
+  const int last_blk = (ctx - 1) / KV_BS;
+  const int32_t* trow = table + (int64_t)b * mbs;
+  const int QD = Hq * HD;
+
+  f16x8 qf[GH][NKF];
+#pragma unroll
+  for (int hh = 0; hh < GH; ++hh)
+#pragma unroll
+    for (int f = 0; f < NKF; ++f)
+      qf[hh][f] = as_f16x8(*reinterpret_cast<const uint4*>(qp + (row0 + my_q) * QD + (h0 + hh) * HD + f * 32 + g * 8));
+
+  f32x4 oacc[GH][NVF];
+  float m_run[GH], l_run[GH];
+#pragma unroll
+  for (int hh = 0; hh < GH; ++hh) {
+    m_run[hh] = NEG_INF;
+    l_run[hh] = 0.f;
+#pragma unroll
+    for (int f = 0; f < NVF; ++f) oacc[hh][f] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int64_t blk_elems = (int64_t)KV_BS * HD;
+  for (int pr = 0; pr < npairs; ++pr) {
+    const int base = pr * 32;
+    const int bi0 = base / KV_BS;
+    const int bi1 = min(bi0 + 1, last_blk);
+    const int64_t off0 = ((int64_t)trow[bi0] * Hkv + j) * blk_elems;
+    const int64_t off1 = ((int64_t)trow[bi1] * Hkv + j) * blk_elems;
+    uint4 kf0[NKF], kf1[NKF];
+    uint2 vf0[NVF], vf1[NVF];
+#pragma unroll
+    for (int f = 0; f < NKF; ++f) {
+      kf0[f] = *reinterpret_cast<const uint4*>(kplane + off0 + (f * 64 + lane) * 8);
+      kf1[f] = *reinterpret_cast<const uint4*>(kplane + off1 + (f * 64 + lane) * 8);
+    }
+#pragma unroll
+    for (int f = 0; f < NVF; ++f) {
+      vf0[f] = *reinterpret_cast<const uint2*>(vplane + off0 + (f * 64 + lane) * 4);
+      vf1[f] = *reinterpret_cast<const uint2*>(vplane + off1 + (f * 64 + lane) * 4);
+    }
+    if (base + 32 > ctx) {  // slots past the end of the sequence may hold anything: keep them out of the MFMA
+      const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
+      const uint32_t a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
+      const uint32_t a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
+      const uint32_t b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
+      const uint32_t b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
+#pragma unroll
+      for (int f = 0; f < NVF; ++f) {
+        vf0[f].x &= a01; vf0[f].y &= a23;
+        vf1[f].x &= b01; vf1[f].y &= b23;
+      }
+    }
+#pragma unroll
+    for (int hh = 0; hh < GH; ++hh) {
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int f = 0; f < NKF; ++f) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qf[hh][f], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qf[hh][f], s1, 0, 0, 0);
+      }
+      float sc[8];
+      float mx = NEG_INF;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sc[i] = (base + 4 * g + i <= qpos) ? s0[i] * scale_log2 : NEG_INF;
+        sc[4 + i] = (base + 16 + 4 * g + i <= qpos) ? s1[i] * scale_log2 : NEG_INF;
+        mx = fmaxf(mx, fmaxf(sc[i], sc[4 + i]));
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[hh], mx);
+      // a query whose visible keys all lie in later pairs has m_new = -inf here: keep its state untouched
+      const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - m_use);
+      union { uint16_t s[8]; f16x8 v; } pb;
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float pv = __builtin_amdgcn_exp2f(sc[i] - m_use);
+        psum += pv;
+        pb.s[i] = f32_to_f16_sat(pv);
+      }
+      l_run[hh] = l_run[hh] * alpha + psum;
+      m_run[hh] = m_new;
+#pragma unroll
+      for (int f = 0; f < NVF; ++f) {
+        uint4 a = make_uint4(vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y);
+        oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
+        oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[hh][f], 0, 0, 0);
+      }
+    }
+  }
+  if (n >= nq) return;
+#pragma unroll
+  for (int hh = 0; hh < GH; ++hh) {
+    float l = l_run[hh];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int f = 0; f < NVF; ++f) {
+      union { uint16_t s[4]; uint2 v; } o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(oacc[hh][f][i] * inv);
+      *reinterpret_cast<uint2*>(op + (row0 + n) * QD + (h0 + hh) * HD + f * 16 + g * 4) = o.v;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host side
+
+static bool g_attr_set = false;
+static void set_smem_attrs() {
+  if (g_attr_set) return;
+  const int bytes = 2 * PG_STAGE_UNITS * 16;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_QKV>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  g_attr_set = true;
+}
+
+template <int EPI>
+static void launch_pgemm(PGemmP& p, hipStream_t st) {
+  p.n_tt = (p.T + 255) / 256;
+  p.n_rt = (p.NRG + 15) / 16;
+  const int bytes = 2 * PG_STAGE_UNITS * 16;
+  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), bytes, st, p);
+}
+
+template <int HD>
+static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* vplane, const int32_t* qlens, const int32_t* lens,
+                         const int32_t* table, int max_tiles, hipStream_t st) {
+  const int G = m->G;
+  const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  dim3 grid(max_tiles, m->Hkv, G / GH), block(256);
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+  const int32_t* cum_rows = m->meta + 16;
+#define PATTN(GH_)                                                                                                                 \
+  hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, qlens, lens, table, \
+                     (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, G, m->tile_seq, m->tile_q0, m->meta, cum_rows, scale_log2,      \
+                     (uint16_t*)m->op)
+  if (GH == 4) PATTN(4); else if (GH == 2) PATTN(2); else PATTN(1);
+#undef PATTN
+}
+
+int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const int32_t* lens, const int32_t* table, int batch, int T,
+                hipStream_t st) {
+  set_smem_attrs();
+  const int d = m->d;
+  int32_t* cum = m->meta + 16;
+  hipLaunchKernelGGL(prefill_meta_kernel, dim3(1), dim3(1024), 0, st, tok, qlens, lens, batch, T, m->row_seq, m->row_pos, m->tile_seq,
+                     m->tile_q0, m->meta, m->last_tok, cum);
+  if (m->cfg.weight_dtype == WWW_DTYPE_F32)
+    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(T), dim3(256), 0, st, tok, (const float*)m->embed, d, m->hp);
+  else
+    hipLaunchKernelGGL(embed_rows_kernel<uint16_t>, dim3(T), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d, m->hp);
+  const int max_tiles = T / ATTN_TQ + batch;
+  for (int l = 0; l < m->L; ++l) {
+    const LayerW& w = m->layers[l];
+    uint16_t* kplane = (uint16_t*)m->kv + (int64_t)(2 * l) * m->kv_plane;
+    uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
+    hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.attn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
+    {
+      PGemmP p = {};
+      p.W = (const uint4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
+      p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
+      launch_pgemm<PEPI_QKV>(p, st);
+    }
+    if (l == m->L - 1) break;  // only this layer's keys and values are still needed
+    if (m->hd == 128) launch_pattn<128>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
+    else launch_pattn<64>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
+    {
+      PGemmP p = {};
+      p.W = (const uint4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const uint16_t*)m->op; p.ldx = m->QD; p.T = T;
+      p.hp = m->hp; p.d = d;
+      launch_pgemm<PEPI_RESID>(p, st);
+    }
+    hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.ffn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
+    {
+      PGemmP p = {};
+      p.W = (const uint4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
+      launch_pgemm<PEPI_SWIGLU>(p, st);
+    }
+    {
+      PGemmP p = {};
+      p.W = (const uint4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const uint16_t*)m->ap; p.ldx = m->Fp; p.T = T;
+      p.hp = m->hp; p.d = d;
+      launch_pgemm<PEPI_RESID>(p, st);
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("prefill launch failed: %s", hipGetErrorString(e));
+    return WWW_E_HIP;
+  }
+  return WWW_OK;
+}
