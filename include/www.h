@@ -62,8 +62,8 @@ extern "C" {
 
 typedef struct www_model www_model; /* opaque handle */
 
-/* Model shape and capacities.  Supported: head_dim in {64, 128}; d_model % 32 == 0; ffn_dim % 16 == 0;
- * vocab % 16 == 0; n_q_heads % n_kv_heads == 0 with a group size <= 16; kv_block_size == 16. */
+/* Model shape and capacities.  Supported: head_dim in {64, 128}; d_model % 128 == 0 and <= 8192; ffn_dim % 16 == 0;
+ * vocab % 16 == 0; n_q_heads / n_kv_heads in {1, 2, 4, 8}; kv_block_size == 16. */
 typedef struct {
   uint32_t abi_version; /* WWW_ABI_VERSION */
   uint32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
@@ -129,6 +129,16 @@ int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, 
  * stream.  which: 0 = residual stream of the decode path [batch][d_model].
  * Errors: INVALID_ARG, HIP. */
 int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream);
+
+/* Benchmark hook: per-kernel timing of decode steps.  While enabled, www_decode_step launches its
+ * kernels one by one (no graph replay) with a HIP event in front of each; www_debug_profile_read
+ * synchronises the stream and returns, for the 8 kernel classes
+ *   0 embedding, 1 QKV GEMM, 2 decode attention, 3 O-projection GEMM, 4 gate/up GEMM, 5 down GEMM,
+ *   6 output-head GEMM, 7 argmax,
+ * the accumulated milliseconds (ms_host[8]) and number of launches (launches_host[8]) since the last
+ * read, then clears them.  Errors: INVALID_ARG, HIP. */
+int www_debug_profile(www_model* m, int32_t enable);
+int www_debug_profile_read(www_model* m, float* ms_host, int32_t* launches_host, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -140,12 +140,15 @@ class OracleModel:
         self.max_seqs, self.max_ctx, self.num_blocks = max_seqs, max_ctx, num_blocks
 
     def close(self):
-        if self._h:
+        if getattr(self, "_h", None):
             lib().orc_free(self._h)
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the module globals may already be gone
+            pass
 
     def set_kv_mode(self, paged: bool):
         lib().orc_set_kv_mode(self._h, 1 if paged else 0)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libwww.so")
 ABI_VERSION = 1
 E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP = -1, -2, -3, -4, -5
 EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_model_free", "www_last_error",
-           "www_debug_slots", "www_debug_read")
+           "www_debug_slots", "www_debug_read", "www_debug_profile", "www_debug_profile_read")
 
 
 class WwwConfig(ctypes.Structure):
@@ -51,7 +51,10 @@ def _load_library():
     L.www_last_error.restype = ctypes.c_char_p
     L.www_debug_slots.argtypes = [vp, vp, i32, vp, vp]
     L.www_debug_read.argtypes = [vp, i32, vp, ctypes.c_uint64, vp]
-    for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read"):
+    L.www_debug_profile.argtypes = [vp, i32]
+    L.www_debug_profile_read.argtypes = [vp, vp, vp, vp]
+    for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read",
+                 "www_debug_profile", "www_debug_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -144,3 +147,18 @@ def www_debug_read(model: Model, which: int, n_floats: int, stream=None):
     out = torch.empty(n_floats, dtype=torch.float32)
     _check(lib.www_debug_read(model._h, which, out.data_ptr(), n_floats, _stream(stream)))
     return out
+
+
+KERNEL_CLASSES = ("embed", "qkv_gemm", "decode_attention", "o_gemm", "gate_up_gemm", "down_gemm", "lm_head_gemm", "argmax")
+
+
+def www_debug_profile(model: Model, enable: bool):
+    _check(lib.www_debug_profile(model._h, 1 if enable else 0))
+
+
+def www_debug_profile_read(model: Model, stream=None):
+    """-> {class name: (total ms, launches)} since the last read"""
+    ms = (ctypes.c_float * 8)()
+    n = (ctypes.c_int32 * 8)()
+    _check(lib.www_debug_profile_read(model._h, ms, n, _stream(stream)))
+    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}

@@ -10,10 +10,36 @@
 
 #include "common.h"
 
+// the library is built with hidden visibility; only the C ABI is exported
+#define WWW_EXPORT extern "C" __attribute__((visibility("default")))
+
 int decode_gemm_ksplit(int NRG, int KB, int MT);
 int decode_MT(int batch);
 
 static thread_local char g_err[512] = "";
+
+// Benchmark hook: while enabled, decode steps run eagerly and an event is recorded in front of every
+// kernel; the elapsed time between consecutive events is charged to the class of the kernel in between.
+struct DecodeProfiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> cls;
+  size_t used = 0;
+};
+
+void prof_mark(www_model* m, int cls, hipStream_t st) {
+  DecodeProfiler* p = m->prof;
+  if (!p || !p->on) return;
+  if (p->used == p->ev.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    p->ev.push_back(e);
+    p->cls.push_back(cls);
+  }
+  p->cls[p->used] = cls;
+  (void)hipEventRecord(p->ev[p->used], st);
+  ++p->used;
+}
 
 void set_error(const char* fmt, ...) {
   va_list ap;
@@ -40,7 +66,8 @@ static int check_config(const www_config* c) {
   else if (c->d_model % 128 || c->d_model > 128 * SSQ_TILES) why = "d_model must be a multiple of 128, at most 8192";
   else if (c->ffn_dim % 16) why = "ffn_dim must be a multiple of 16";
   else if (c->vocab % 16) why = "vocab must be a multiple of 16";
-  else if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 16) why = "n_q_heads must be a multiple of n_kv_heads, group size <= 16";
+  else if (c->n_q_heads % c->n_kv_heads) why = "n_q_heads must be a multiple of n_kv_heads";
+  else if (int g = c->n_q_heads / c->n_kv_heads; g != 1 && g != 2 && g != 4 && g != 8) why = "query heads per kv head must be 1, 2, 4 or 8";
   else if (c->kv_block_size != KV_BS) why = "kv_block_size must be 16";
   else if (c->weight_dtype > 1) why = "weight_dtype must be 0 (fp32) or 1 (bf16)";
   else if (c->max_batch == 0 || c->max_batch > 1024) why = "max_batch must be in 1..1024";
@@ -156,7 +183,7 @@ static uint64_t blob_bytes(const www_config* c) {
   return off;
 }
 
-extern "C" int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_bytes, uint64_t* kv_pool_bytes, uint64_t* workspace_bytes) {
+WWW_EXPORT int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_bytes, uint64_t* kv_pool_bytes, uint64_t* workspace_bytes) {
   int rc = check_config(cfg);
   if (rc) return rc;
   const Dims s = dims_of(cfg);
@@ -168,7 +195,7 @@ extern "C" int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_byte
   return WWW_OK;
 }
 
-extern "C" int www_model_load(const www_config* cfg, const void* weights_dev, void* kv_pool_dev, void* workspace_dev, void* hip_stream,
+WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, void* kv_pool_dev, void* workspace_dev, void* hip_stream,
                               www_model** out) {
   int rc = check_config(cfg);
   if (rc) return rc;
@@ -265,7 +292,7 @@ extern "C" int www_model_load(const www_config* cfg, const void* weights_dev, vo
   return WWW_OK;
 }
 
-extern "C" int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
+WWW_EXPORT int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
                            const int32_t* block_table_dev, int32_t batch, int32_t total_q_tokens, float* logits_dev,
                            int32_t* next_tokens_dev, void* hip_stream) {
   if (!m || !tokens_dev || !q_lens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
@@ -280,14 +307,14 @@ extern "C" int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_
   return run_decode(m, m->last_tok, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
 }
 
-extern "C" int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
+WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
                                int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream) {
   if (!m || !last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch < 0) { set_error("negative batch"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
   if (batch == 0) return WWW_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (!m->use_graph || st == nullptr)  // the legacy default stream cannot be captured
+  if (!m->use_graph || st == nullptr || (m->prof && m->prof->on))  // the legacy default stream cannot be captured
     return run_decode(m, last_tokens_dev, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
 
   for (int i = 0; i < m->n_graphs; ++i) {
@@ -321,23 +348,27 @@ extern "C" int www_decode_step(www_model* m, const int32_t* last_tokens_dev, con
   return WWW_OK;
 }
 
-extern "C" void www_model_free(www_model* m) {
+WWW_EXPORT void www_model_free(www_model* m) {
   if (!m) return;
   for (int i = 0; i < m->n_graphs; ++i) (void)hipGraphExecDestroy(m->graphs[i].exec);
+  if (m->prof) {
+    for (hipEvent_t e : m->prof->ev) (void)hipEventDestroy(e);
+    delete m->prof;
+  }
   delete[] m->graphs;
   delete[] m->layers;
   delete m;
 }
 
-extern "C" const char* www_last_error(void) { return g_err; }
+WWW_EXPORT const char* www_last_error(void) { return g_err; }
 
-extern "C" int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream) {
+WWW_EXPORT int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream) {
   if (!table_row_dev || !positions_dev || !slots_dev || n < 0) { set_error("bad argument"); return WWW_E_INVALID_ARG; }
   if (launch_debug_slots(table_row_dev, positions_dev, n, slots_dev, (hipStream_t)hip_stream)) { set_error("launch failed"); return WWW_E_HIP; }
   return WWW_OK;
 }
 
-extern "C" int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream) {
+WWW_EXPORT int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream) {
   if (!m || !dst_host) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   const float* src = nullptr;
   uint64_t cap = 0;
@@ -346,5 +377,30 @@ extern "C" int www_debug_read(www_model* m, int32_t which, float* dst_host, uint
   if (n_floats > cap) { set_error("buffer holds %llu floats", (unsigned long long)cap); return WWW_E_INVALID_ARG; }
   HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
   HIP_TRY(hipMemcpy(dst_host, src, n_floats * 4, hipMemcpyDeviceToHost));
+  return WWW_OK;
+}
+
+WWW_EXPORT int www_debug_profile(www_model* m, int32_t enable) {
+  if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
+  if (!m->prof) m->prof = new DecodeProfiler();
+  m->prof->on = enable != 0;
+  m->prof->used = 0;
+  return WWW_OK;
+}
+
+WWW_EXPORT int www_debug_profile_read(www_model* m, float* ms_host, int32_t* launches_host, void* hip_stream) {
+  if (!m || !m->prof || !ms_host || !launches_host) { set_error("profiling was never enabled, or NULL argument"); return WWW_E_INVALID_ARG; }
+  HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+  for (int i = 0; i < PK_COUNT; ++i) { ms_host[i] = 0.f; launches_host[i] = 0; }
+  DecodeProfiler* p = m->prof;
+  for (size_t i = 0; i + 1 < p->used; ++i) {
+    int c = p->cls[i];
+    if (c < 0 || c >= PK_COUNT) continue;  // -1 marks the end of a step
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, p->ev[i], p->ev[i + 1]));
+    ms_host[c] += ms;
+    launches_host[c] += 1;
+  }
+  p->used = 0;
   return WWW_OK;
 }

@@ -7,6 +7,8 @@
 #include "../../include/www.h"
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // 16 raw bytes (native vector: stays in registers)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
@@ -115,11 +117,16 @@ struct www_model {
   GraphEntry* graphs;
   int n_graphs;
   int use_graph;
+  struct DecodeProfiler* prof;  // per-kernel-class timing of eager decode steps (benchmark hook), or null
 };
 
 #define SSQ_TILES 64       // most row tiles of a residual-producing GEMM (d_model / 128)
 #define GEMM_TILE_ROWS 128 // rows of W per workgroup of the skinny GEMM
 #define MAX_KSPLIT 16
+
+// decode kernel classes reported by the profiling hook
+enum { PK_EMBED = 0, PK_QKV, PK_ATTN, PK_OPROJ, PK_GATEUP, PK_DOWN, PK_LMHEAD, PK_ARGMAX, PK_COUNT };
+void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in front of the next launch when profiling is on
 
 // host-side launchers (decode.hip / prefill.hip / pack.hip)
 void set_error(const char* fmt, ...);

@@ -2,17 +2,48 @@
 // RMSNorm scale / rotary + KV-cache write / SwiGLU / residual epilogues, split-KV paged attention,
 // argmax.  Activations travel between kernels as hi/lo fp16 pairs already laid out as MFMA B
 // operands, so every GEMM's inner loop is loads and MFMAs only.
+#include <stdlib.h>
+
 #include "common.h"
 
 #define NEG_INF (-__builtin_inff())
 
-__device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
-__device__ __forceinline__ float rstd_of(const float* __restrict__ ssq, int n_tiles, int stride, int t, float inv_dim, float eps) {
+// sum of the per-tile partial sums of squares of token t, added in tile order (reproducible); loads go out eight at a
+// time so the chain costs a few memory round trips instead of one per tile
+__device__ __forceinline__ float ssq_total(const float* __restrict__ ssq, int n_tiles, int stride, int t) {
   float s = 0.f;
-  for (int i = 0; i < n_tiles; ++i) s += ssq[i * stride + t];  // fixed order: reproducible
-  return rsqrtf(s * inv_dim + eps);
+  for (int i0 = 0; i0 < n_tiles; i0 += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = ssq[min(i0 + u, n_tiles - 1) * stride + t];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + u < n_tiles) s += v[u];
+  }
+  return s;
 }
+
+// Cross-workgroup hand-over of partial results inside one kernel.  Partial tiles are written and read with
+// device-scope relaxed atomic accesses, which go through to memory shared by all XCDs instead of living in one
+// XCD's write-back L2; the producer waits for its stores to complete, the workgroup syncs, and one thread bumps a
+// device-scope counter.  This avoids device-scope fences, whose whole-L2 write-back / invalidate costs tens of
+// microseconds per kernel here.
+__device__ __forceinline__ void store_shared_f32x4(float* p, f32x4 v) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 load_shared_f32x4(const float* p) {
+  f32x4 v;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return v;
+}
+__device__ __forceinline__ void store_shared_f32(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float load_shared_f32(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// all of this wavefront's earlier memory operations have completed
+__device__ __forceinline__ void wait_own_memory_ops() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
 
 // offset (in elements) of column k of token t in a packed activation buffer with MT token groups
 __device__ __forceinline__ int64_t packed_x_offset(int k, int t, int MT, int hl) {
@@ -31,7 +62,7 @@ __global__ __launch_bounds__(256) void embed_pack_kernel(const int32_t* __restri
   float local = 0.f;
   for (int o = threadIdx.x; o < d / 8; o += blockDim.x) {
     int k = o * 8;
-    union { uint16_t s[8]; uint4 v; } hi, lo;
+    union { uint16_t s[8]; u32x4 v; } hi, lo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float x;
@@ -41,8 +72,8 @@ __global__ __launch_bounds__(256) void embed_pack_kernel(const int32_t* __restri
       local += x * x;
       split_f16(x * gain[k + e], hi.s[e], lo.s[e]);
     }
-    *reinterpret_cast<uint4*>(xq + packed_x_offset(k, t, MT, 0)) = hi.v;
-    *reinterpret_cast<uint4*>(xq + packed_x_offset(k, t, MT, 1)) = lo.v;
+    *reinterpret_cast<u32x4*>(xq + packed_x_offset(k, t, MT, 0)) = hi.v;
+    *reinterpret_cast<u32x4*>(xq + packed_x_offset(k, t, MT, 1)) = lo.v;
   }
   __shared__ float red[256];
   red[threadIdx.x] = local;
@@ -59,10 +90,10 @@ __global__ __launch_bounds__(256) void embed_pack_kernel(const int32_t* __restri
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
 struct GemmP {
-  const uint4* W;    // packed weights, 16-byte units
-  const uint4* Wlo;  // low-order plane (fp32 sources) or null
+  const u32x4* W;    // packed weights, 16-byte units
+  const u32x4* Wlo;  // low-order plane (fp32 sources) or null
   int NRG, KB;       // row groups of 16, k blocks of 32
-  const uint4* X;    // packed activations
+  const u32x4* X;    // packed activations
   int MT, M;         // token groups in X, valid tokens
   int kb_per_split, ksplit;
   float* partial;    // [ksplit][MT*16][NRG*16]
@@ -95,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   constexpr int R = 2, KC = 4, WP = WSPLIT ? 2 : 1;
   constexpr int CHUNK_UNITS = KC * MTK * 128;      // 16-byte units of activations per k chunk
   constexpr int NSTG = CHUNK_UNITS / 256;
-  __shared__ uint4 lds[2][CHUNK_UNITS];
+  __shared__ u32x4 lds[2][CHUNK_UNITS];
   // after the main loop the staging buffers are dead and are reused for the epilogue's small reductions
   float(*red)[64] = reinterpret_cast<float(*)[64]>(&lds[0][0]);
   volatile int* s_last = reinterpret_cast<volatile int*>(&lds[1][0]);
@@ -118,46 +149,61 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 #pragma unroll
     for (int tb = 0; tb < MTK; ++tb) acc[r][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 wA[KC][R][WP], wB[KC][R][WP], stg[NSTG];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  // Inputs of the epilogue that hang off dependent loads (RMSNorm scale; position and KV slot of each token) are
+  // fetched now, so their latency hides behind the main loop.
+  float scale_pre[MTK];
+  int pos_pre[MTK];
+  int64_t slot_pre[MTK];
+#pragma unroll
+  for (int tb = 0; tb < MTK; ++tb) {
+    const int t = (tb0 + tb) * 16 + (lane & 15);
+    const bool tok_ok = t < p.M;
+    scale_pre[tb] = 1.f;
+    pos_pre[tb] = 0;
+    slot_pre[tb] = 0;
+    if (p.ssq_in && tok_ok) scale_pre[tb] = rsqrtf(ssq_total(p.ssq_in, p.n_ssq_in, p.ssq_stride, t) * p.inv_dim + p.eps);
+    if constexpr (EPI == EPI_QKV) {
+      if (tok_ok) {
+        pos_pre[tb] = p.seq_lens[t] - 1;
+        slot_pre[tb] = kv_slot(p.table + (int64_t)t * p.mbs, pos_pre[tb]);
+      }
+    }
+  }
 
-  auto load_w = [&](uint4(&w)[KC][R][WP], int c) {
+  u32x4 wA[KC][R][WP], wB[KC][R][WP], stg[NSTG];
+
+  // Loads past the end of this split's k range are redirected to its last valid block (in bounds) and the
+  // matching MFMAs are skipped in compute(): no per-element selects in the streaming loop.
+  auto load_w = [&](u32x4(&w)[KC][R][WP], int c) {
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
-      int kb = kb_begin + c * KC + kk;
-      bool ok = kb < kb_end;
-      int kbc = ok ? kb : kb_end - 1;
+      const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        int64_t idx = ((int64_t)rgc[r] * p.KB + kbc) * 64 + lane;
-        uint4 v = p.W[idx];
-        w[kk][r][0] = ok ? v : zero4;
-        if constexpr (WSPLIT) {
-          uint4 v2 = p.Wlo[idx];
-          w[kk][r][1] = ok ? v2 : zero4;
-        }
+        const int64_t idx = ((int64_t)rgc[r] * p.KB + kbc) * 64 + lane;
+        w[kk][r][0] = p.W[idx];
+        if constexpr (WSPLIT) w[kk][r][1] = p.Wlo[idx];
       }
     }
   };
-  auto load_stage = [&](int c) {
+  auto load_stage = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NSTG; ++i) {
-      int u = tid + i * 256;
-      int kk = u / (MTK * 128), within = u % (MTK * 128);
-      int kb = kb_begin + c * KC + kk;
-      bool ok = kb < kb_end;
-      int kbc = ok ? kb : kb_end - 1;
-      uint4 v = p.X[((int64_t)kbc * p.MT + tb0) * 128 + within];
-      stg[i] = ok ? v : zero4;
+      const int u = tid + i * 256;
+      const int kk = u / (MTK * 128), within = u % (MTK * 128);
+      const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
+      stg[i] = p.X[((int64_t)kbc * p.MT + tb0) * 128 + within];
     }
   };
-  auto store_stage = [&](int buf) {
+  auto store_stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NSTG; ++i) lds[buf][tid + i * 256] = stg[i];
   };
-  auto compute = [&](uint4(&w)[KC][R][WP], int buf) {
+  // nvalid = k blocks of the chunk that lie inside the range: KC for every chunk but possibly the last
+  auto compute = [&](u32x4(&w)[KC][R][WP], int buf, int nvalid) __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
+      if (kk >= nvalid) break;
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
         f16x8 bhi = as_f16x8(lds[buf][(kk * MTK + tb) * 128 + lane]);
@@ -173,24 +219,45 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     }
   };
 
+  // Software pipeline: while chunk c is multiplied out of LDS buffer c&1 and register set A/B, chunk c+1 is
+  // already on its way from HBM.  The steady-state loop has no conditional loads, so the new loads can stay
+  // in flight across the MFMAs of the current chunk; the last one or two chunks are peeled.
   if (nchunks > 0) {
+    const int last_valid = (kb_end - kb_begin) - (nchunks - 1) * KC;  // k blocks in the final chunk
     load_stage(0);
     load_w(wA, 0);
     store_stage(0);
     __syncthreads();
-    for (int c = 0; c < nchunks; c += 2) {
-      bool has1 = c + 1 < nchunks;
-      if (has1) { load_stage(c + 1); load_w(wB, c + 1); }
-      compute(wA, 0);
-      if (has1) store_stage(1);
+    int c = 0;
+    for (; c + 2 < nchunks; c += 2) {
+      load_stage(c + 1);
+      load_w(wB, c + 1);
+      __builtin_amdgcn_sched_barrier(0);  // keep the prefetch in front of the MFMAs it overlaps with
+      compute(wA, 0, KC);
+      __builtin_amdgcn_sched_barrier(0);
+      store_stage(1);
       __syncthreads();
-      if (!has1) break;
-      bool has2 = c + 2 < nchunks;
-      if (has2) { load_stage(c + 2); load_w(wA, c + 2); }
-      compute(wB, 1);
-      if (has2) store_stage(0);
+      load_stage(c + 2);
+      load_w(wA, c + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(wB, 1, KC);
+      __builtin_amdgcn_sched_barrier(0);
+      store_stage(0);
       __syncthreads();
     }
+    if (c + 1 < nchunks) {
+      load_stage(c + 1);
+      load_w(wB, c + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(wA, 0, KC);
+      __builtin_amdgcn_sched_barrier(0);
+      store_stage(1);
+      __syncthreads();
+      compute(wB, 1, last_valid);
+    } else {
+      compute(wA, 0, last_valid);
+    }
+    __syncthreads();
   }
 
   // accumulator layout: acc[r][tb][i] = Y^T[row][token], row = (rg0+r)*16 + (lane/16)*4 + i, token = (tb0+tb)*16 + lane%16
@@ -206,32 +273,47 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
         int t = (tb0 + tb) * 16 + tsub;
-        float4 v = make_float4(acc[r][tb][0], acc[r][tb][1], acc[r][tb][2], acc[r][tb][3]);
-        *reinterpret_cast<float4*>(p.partial + ((int64_t)split * (p.MT * 16) + t) * Npad + (rg0 + r) * 16 + rsub) = v;
+        store_shared_f32x4(p.partial + ((int64_t)split * (p.MT * 16) + t) * Npad + (rg0 + r) * 16 + rsub, acc[r][tb]);
       }
     }
-    __threadfence();
+    wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
-      int old = atomicAdd(&p.counters[zb * gridDim.x + tile], 1);
+      int old = __hip_atomic_fetch_add(&p.counters[zb * gridDim.x + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (old == p.ksplit - 1);
     }
     __syncthreads();
     if (!*s_last) return;
-    __threadfence();
-    if (tid == 0) p.counters[zb * gridDim.x + tile] = 0;
+    if (tid == 0) __hip_atomic_store(&p.counters[zb * gridDim.x + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int tb = 0; tb < MTK; ++tb) {
-        acc[r][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (rg0 + r >= p.NRG) continue;
-        int t = (tb0 + tb) * 16 + tsub;
-        for (int s = 0; s < p.ksplit; ++s) {
-          float4 v = *reinterpret_cast<const float4*>(p.partial + ((int64_t)s * (p.MT * 16) + t) * Npad + (rg0 + r) * 16 + rsub);
-          acc[r][tb][0] += v.x; acc[r][tb][1] += v.y; acc[r][tb][2] += v.z; acc[r][tb][3] += v.w;
-        }
+      for (int tb = 0; tb < MTK; ++tb) acc[r][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // partial tiles are added in split order (reproducible); loads are issued four splits at a time so that
+    // the reduction is not one memory round trip per split
+    for (int s0 = 0; s0 < p.ksplit; s0 += 4) {
+      f32x4 pv[4][R][MTK];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int sidx = min(s0 + u, p.ksplit - 1);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int tb = 0; tb < MTK; ++tb) {
+            const int t = (tb0 + tb) * 16 + tsub;
+            const int rgs = min(rg0 + r, p.NRG - 1);
+            pv[u][r][tb] = load_shared_f32x4(p.partial + ((int64_t)sidx * (p.MT * 16) + t) * Npad + rgs * 16 + rsub);
+          }
       }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (s0 + u >= p.ksplit) break;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int tb = 0; tb < MTK; ++tb) acc[r][tb] += pv[u][r][tb];
+      }
+    }
   }
 
   float ssq_local[MTK];
@@ -242,21 +324,20 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   for (int tb = 0; tb < MTK; ++tb) {
     const int t = (tb0 + tb) * 16 + tsub;
     const bool tok_ok = t < p.M;
-    float scale = 1.f;
-    if (p.ssq_in && tok_ok) scale = rstd_of(p.ssq_in, p.n_ssq_in, p.ssq_stride, t, p.inv_dim, p.eps);
+    const float scale = scale_pre[tb];
 
     if constexpr (EPI == EPI_SWIGLU) {
       if (tok_ok && rg0 + 1 < p.NRG) {
         int f0 = (rg0 >> 1) * 16 + rsub;
-        union { uint16_t s[4]; uint2 v; } hi, lo;
+        union { uint16_t s[4]; u32x2 v; } hi, lo;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float g = acc[0][tb][i] * scale, u = acc[1][tb][i] * scale;
           float a = g / (1.f + __expf(-g)) * u;
           split_f16(a, hi.s[i], lo.s[i]);
         }
-        *reinterpret_cast<uint2*>(p.xa + packed_x_offset(f0, t, p.MT, 0)) = hi.v;
-        *reinterpret_cast<uint2*>(p.xa + packed_x_offset(f0, t, p.MT, 1)) = lo.v;
+        *reinterpret_cast<u32x2*>(p.xa + packed_x_offset(f0, t, p.MT, 0)) = hi.v;
+        *reinterpret_cast<u32x2*>(p.xa + packed_x_offset(f0, t, p.MT, 1)) = lo.v;
       }
     } else {
 #pragma unroll
@@ -275,16 +356,16 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
           float hn[4] = {hv.x + v[0], hv.y + v[1], hv.z + v[2], hv.w + v[3]};
           float gn[4] = {gv.x, gv.y, gv.z, gv.w};
           *reinterpret_cast<float4*>(p.h + (int64_t)t * p.d + n0) = make_float4(hn[0], hn[1], hn[2], hn[3]);
-          union { uint16_t s[4]; uint2 v; } hi, lo;
+          union { uint16_t s[4]; u32x2 v; } hi, lo;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             ssq_local[tb] += hn[i] * hn[i];
             split_f16(hn[i] * gn[i], hi.s[i], lo.s[i]);
           }
-          *reinterpret_cast<uint2*>(p.xnext + packed_x_offset(n0, t, p.MT, 0)) = hi.v;
-          *reinterpret_cast<uint2*>(p.xnext + packed_x_offset(n0, t, p.MT, 1)) = lo.v;
+          *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 0)) = hi.v;
+          *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 1)) = lo.v;
         } else {  // EPI_QKV
-          const int pos = p.seq_lens[t] - 1;
+          const int pos = pos_pre[tb];
           const int rot_rows = (p.Hq + p.Hkv) * p.hd;
           const int head = n0 / p.hd, c0 = n0 % p.hd;
           if (n0 < rot_rows) {
@@ -300,15 +381,15 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
           if (head < p.Hq) {
             *reinterpret_cast<float4*>(p.q + (int64_t)t * (p.Hq * p.hd) + n0) = make_float4(v[0], v[1], v[2], v[3]);
           } else {
-            const int64_t slot = kv_slot(p.table + (int64_t)t * p.mbs, pos);
+            const int64_t slot = slot_pre[tb];
             const int64_t blk = slot / KV_BS;
             const int tok = (int)(slot % KV_BS);
             if (head < p.Hq + p.Hkv) {
               const int j = head - p.Hq;
-              union { uint16_t s[4]; uint2 v; } kb16;
+              union { uint16_t s[4]; u32x2 v; } kb16;
 #pragma unroll
               for (int i = 0; i < 4; ++i) kb16.s[i] = f32_to_f16_sat(v[i]);
-              *reinterpret_cast<uint2*>(p.kplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = kb16.v;
+              *reinterpret_cast<u32x2*>(p.kplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = kb16.v;
             } else {
               const int j = head - p.Hq - p.Hkv;
               uint16_t* dst = p.vplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd);
@@ -344,10 +425,10 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 //   O^T = V^T P^T (head_dim x heads).  The G query heads of the group share every K/V byte.
 // Partial results (m, l, unnormalised o) of all splits of a (sequence, kv head) are merged by the
 // wavefront that finishes last, which also writes the packed hi/lo operand of the O projection.
-template <int HD>
+template <int HD, int G>
 __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict__ q, const uint16_t* __restrict__ kplane,
                                                           const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
-                                                          const int32_t* __restrict__ table, int mbs, int G, int Hq, int Hkv, int kps,
+                                                          const int32_t* __restrict__ table, int mbs, int Hq, int Hkv, int kps,
                                                           float qscale, float* __restrict__ part, int* __restrict__ counters,
                                                           uint16_t* __restrict__ xo, int MT) {
   constexpr int NKF = HD / 32;  // K fragments per block
@@ -393,17 +474,17 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
     const int bi1 = min(bi0 + 1, last_blk);
     const int64_t off0 = ((int64_t)trow[bi0] * Hkv + j) * blk_elems;
     const int64_t off1 = ((int64_t)trow[bi1] * Hkv + j) * blk_elems;
-    uint4 kf0[NKF], kf1[NKF];
-    uint2 vf0[NVF], vf1[NVF];
+    u32x4 kf0[NKF], kf1[NKF];
+    u32x2 vf0[NVF], vf1[NVF];
 #pragma unroll
     for (int f = 0; f < NKF; ++f) {
-      kf0[f] = *reinterpret_cast<const uint4*>(kplane + off0 + (f * 64 + lane) * 8);
-      kf1[f] = *reinterpret_cast<const uint4*>(kplane + off1 + (f * 64 + lane) * 8);
+      kf0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
+      kf1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      vf0[f] = *reinterpret_cast<const uint2*>(vplane + off0 + (f * 64 + lane) * 4);
-      vf1[f] = *reinterpret_cast<const uint2*>(vplane + off1 + (f * 64 + lane) * 4);
+      vf0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
+      vf1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
     }
     // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1)
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -451,7 +532,7 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      uint4 a = make_uint4(vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y);
+      u32x4 a = {vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y};
       oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
       oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
     }
@@ -459,47 +540,89 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
 
+  if (nsplit_act == 1) {
+    // the whole context fitted into this split: normalise and emit the packed O-projection operand directly
+    if (n < G) {
+      const float inv = 1.f / l_run;
+#pragma unroll
+      for (int f = 0; f < NVF; ++f) {
+        union { uint16_t s[4]; u32x2 v; } hi, lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) split_f16(oacc[f][i] * inv, hi.s[i], lo.s[i]);
+        const int k = (j * G + n) * HD + f * 16 + g * 4;
+        *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 0)) = hi.v;
+        *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 1)) = lo.v;
+      }
+    }
+    return;
+  }
+
   // park this split's record: [b][j][split][head n][o(HD), m, l]
   float* rec = part + ((((int64_t)b * Hkv + j) * nsplit_max + split) * G) * PSTRIDE;
   if (n < G) {
 #pragma unroll
     for (int f = 0; f < NVF; ++f)
-      *reinterpret_cast<float4*>(rec + n * PSTRIDE + f * 16 + g * 4) = make_float4(oacc[f][0], oacc[f][1], oacc[f][2], oacc[f][3]);
+      store_shared_f32x4(rec + n * PSTRIDE + f * 16 + g * 4, oacc[f]);
     if (g == 0) {
-      rec[n * PSTRIDE + HD] = m_run;
-      rec[n * PSTRIDE + HD + 1] = l_run;
+      store_shared_f32(rec + n * PSTRIDE + HD, m_run);
+      store_shared_f32(rec + n * PSTRIDE + HD + 1, l_run);
     }
   }
-  __threadfence();
+  wait_own_memory_ops();
   int old = 0;
-  if (lane == 0) old = atomicAdd(&counters[b * Hkv + j], 1);
+  if (lane == 0) old = __hip_atomic_fetch_add(&counters[b * Hkv + j], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   old = __shfl(old, 0);
   if (old != nsplit_act - 1) return;
-  __threadfence();
-  if (lane == 0) counters[b * Hkv + j] = 0;
+  if (lane == 0) __hip_atomic_store(&counters[b * Hkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-  // merge all splits (in split order) and emit the packed O-projection operand
+  // Merge all splits in split order.  Lane owns head-dim elements lane + 64*i of every head; records are read
+  // four splits at a time so the merge is not one memory round trip per split.
   const float* recs = part + (((int64_t)b * Hkv + j) * nsplit_max) * G * PSTRIDE;
+  constexpr int NE = HD / 64;
+  float Mh[G], Lh[G], oh[G][NE];
+#pragma unroll
   for (int hh = 0; hh < G; ++hh) {
-    float M = NEG_INF;
-    for (int s = 0; s < nsplit_act; ++s) M = fmaxf(M, recs[((int64_t)s * G + hh) * PSTRIDE + HD]);
-    float Lsum = 0.f;
-    float o[HD / 64];
+    Mh[hh] = NEG_INF;
+    Lh[hh] = 0.f;
 #pragma unroll
-    for (int i = 0; i < HD / 64; ++i) o[i] = 0.f;
-    for (int s = 0; s < nsplit_act; ++s) {
-      const float* r = recs + ((int64_t)s * G + hh) * PSTRIDE;
-      float w = __builtin_amdgcn_exp2f(r[HD] - M);
-      Lsum += r[HD + 1] * w;
+    for (int i = 0; i < NE; ++i) oh[hh][i] = 0.f;
+  }
+  for (int s0 = 0; s0 < nsplit_act; s0 += 4) {
+    float mv[4][G], lv[4][G], ov[4][G][NE];
 #pragma unroll
-      for (int i = 0; i < HD / 64; ++i) o[i] += r[lane + 64 * i] * w;
+    for (int u = 0; u < 4; ++u) {
+      const int sidx = min(s0 + u, nsplit_act - 1);
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        const float* r = recs + ((int64_t)sidx * G + hh) * PSTRIDE;
+        mv[u][hh] = load_shared_f32(r + HD);
+        lv[u][hh] = load_shared_f32(r + HD + 1);
+#pragma unroll
+        for (int i = 0; i < NE; ++i) ov[u][hh][i] = load_shared_f32(r + lane + 64 * i);
+      }
     }
-    const float inv = 1.f / Lsum;
 #pragma unroll
-    for (int i = 0; i < HD / 64; ++i) {
-      int k = (j * G + hh) * HD + lane + 64 * i;
+    for (int u = 0; u < 4; ++u) {
+      if (s0 + u >= nsplit_act) break;
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        const float Mn = fmaxf(Mh[hh], mv[u][hh]);
+        const float a = __builtin_amdgcn_exp2f(Mh[hh] - Mn), w = __builtin_amdgcn_exp2f(mv[u][hh] - Mn);
+        Lh[hh] = Lh[hh] * a + lv[u][hh] * w;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) oh[hh][i] = oh[hh][i] * a + ov[u][hh][i] * w;
+        Mh[hh] = Mn;
+      }
+    }
+  }
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh) {
+    const float inv = 1.f / Lh[hh];
+#pragma unroll
+    for (int i = 0; i < NE; ++i) {
+      const int k = (j * G + hh) * HD + lane + 64 * i;
       uint16_t hi, lo;
-      split_f16(o[i] * inv, hi, lo);
+      split_f16(oh[hh][i] * inv, hi, lo);
       xo[packed_x_offset(k, b, MT, 0)] = hi;
       xo[packed_x_offset(k, b, MT, 1)] = lo;
     }
@@ -535,12 +658,25 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
 // ------------------------------------------------------------------------------------------------
 // Host side
 
+// Workgroups a skinny GEMM should spread over (split-K is used when the row tiles alone are fewer).  Tunable
+// through the environment variable WWW_GEMM_WG_TARGET, read once.
+static int wg_target() {
+  static int v = 0;
+  if (!v) {
+    const char* e = getenv("WWW_GEMM_WG_TARGET");
+    v = e ? atoi(e) : 320;
+    if (v < 1) v = 1;
+  }
+  return v;
+}
+
 static void choose_split(int row_tiles, int zb, int KB, int* ksplit, int* kb_per_split) {
-  int want = 384 / (row_tiles * zb);
+  int want = wg_target() / (row_tiles * zb);
   if (want < 1) want = 1;
   if (want > MAX_KSPLIT) want = MAX_KSPLIT;
   int per = (KB + want - 1) / want;
   per = (per + 3) / 4 * 4;
+  if (per < 8) per = 8;  // at least two k chunks per workgroup, so the load pipeline has something to overlap
   *kb_per_split = per;
   *ksplit = (KB + per - 1) / per;
 }
@@ -577,6 +713,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
                hipStream_t st) {
   const int MT = decode_MT(batch);
   const int d = m->d;
+  prof_mark(m, PK_EMBED, st);
   if (m->cfg.weight_dtype == WWW_DTYPE_F32)
     hipLaunchKernelGGL(embed_pack_kernel<float>, dim3(batch), dim3(256), 0, st, tok, (const float*)m->embed, d, m->layers[0].attn_norm,
                        m->h, m->ssq, (uint16_t*)m->xq, MT);
@@ -592,57 +729,69 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
     {
       GemmP p = {};
-      p.W = (const uint4*)w.wqkv; p.Wlo = (const uint4*)w.wqkv_lo; p.NRG = m->QKVN / 16; p.KB = d / 32;
-      p.X = (const uint4*)m->xq; p.M = batch;
+      p.W = (const u32x4*)w.wqkv; p.Wlo = (const u32x4*)w.wqkv_lo; p.NRG = m->QKVN / 16; p.KB = d / 32;
+      p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.q = m->q; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
       p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
+      prof_mark(m, PK_QKV, st);
       launch_gemm<EPI_QKV>(m, p, MT, st);
     }
     {
       dim3 grid(m->attn_splits, m->Hkv, batch);
-      if (m->hd == 128)
-        hipLaunchKernelGGL(decode_attn_kernel<128>, grid, dim3(64), 0, st, m->q, kplane, vplane, lens, table, (int)m->cfg.max_blocks_per_seq,
-                           m->G, m->Hq, m->Hkv, m->attn_kps, qscale, m->attn_part, m->counters + 65536, (uint16_t*)m->xo, MT);
-      else
-        hipLaunchKernelGGL(decode_attn_kernel<64>, grid, dim3(64), 0, st, m->q, kplane, vplane, lens, table, (int)m->cfg.max_blocks_per_seq,
-                           m->G, m->Hq, m->Hkv, m->attn_kps, qscale, m->attn_part, m->counters + 65536, (uint16_t*)m->xo, MT);
+      prof_mark(m, PK_ATTN, st);
+#define ATTN(HD_, G_)                                                                                                              \
+  hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q, kplane, vplane, lens, table,                       \
+                     (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, qscale, m->attn_part, m->counters + 65536,          \
+                     (uint16_t*)m->xo, MT)
+      if (m->hd == 128) {
+        if (m->G == 1) ATTN(128, 1); else if (m->G == 2) ATTN(128, 2); else if (m->G == 4) ATTN(128, 4); else ATTN(128, 8);
+      } else {
+        if (m->G == 1) ATTN(64, 1); else if (m->G == 2) ATTN(64, 2); else if (m->G == 4) ATTN(64, 4); else ATTN(64, 8);
+      }
+#undef ATTN
     }
     {
       GemmP p = {};
-      p.W = (const uint4*)w.wo; p.Wlo = (const uint4*)w.wo_lo; p.NRG = d / 16; p.KB = m->QD / 32;
-      p.X = (const uint4*)m->xo; p.M = batch;
+      p.W = (const u32x4*)w.wo; p.Wlo = (const u32x4*)w.wo_lo; p.NRG = d / 16; p.KB = m->QD / 32;
+      p.X = (const u32x4*)m->xo; p.M = batch;
       p.h = m->h; p.gain_next = w.ffn_norm; p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.ssq_stride = stride; p.d = d;
+      prof_mark(m, PK_OPROJ, st);
       launch_gemm<EPI_RESID>(m, p, MT, st);
       n_ssq = (d / 16 + 7) / 8;
     }
     {
       GemmP p = {};
-      p.W = (const uint4*)w.wgu; p.Wlo = (const uint4*)w.wgu_lo; p.NRG = 2 * m->F / 16; p.KB = d / 32;
-      p.X = (const uint4*)m->xq; p.M = batch;
+      p.W = (const u32x4*)w.wgu; p.Wlo = (const u32x4*)w.wgu_lo; p.NRG = 2 * m->F / 16; p.KB = d / 32;
+      p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.xa = (uint16_t*)m->xa; p.F = m->F;
+      prof_mark(m, PK_GATEUP, st);
       launch_gemm<EPI_SWIGLU>(m, p, MT, st);
     }
     {
       GemmP p = {};
-      p.W = (const uint4*)w.wd; p.Wlo = (const uint4*)w.wd_lo; p.NRG = d / 16; p.KB = m->Fp / 32;
-      p.X = (const uint4*)m->xa; p.M = batch;
+      p.W = (const u32x4*)w.wd; p.Wlo = (const u32x4*)w.wd_lo; p.NRG = d / 16; p.KB = m->Fp / 32;
+      p.X = (const u32x4*)m->xa; p.M = batch;
       p.h = m->h; p.gain_next = (l + 1 < m->L) ? m->layers[l + 1].attn_norm : m->final_norm;
       p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.ssq_stride = stride; p.d = d;
+      prof_mark(m, PK_DOWN, st);
       launch_gemm<EPI_RESID>(m, p, MT, st);
     }
   }
   float* lg = logits ? logits : m->logits_buf;
   {
     GemmP p = {};
-    p.W = (const uint4*)m->lm_head; p.Wlo = (const uint4*)m->lm_head_lo; p.NRG = m->V / 16; p.KB = d / 32;
-    p.X = (const uint4*)m->xq; p.M = batch;
+    p.W = (const u32x4*)m->lm_head; p.Wlo = (const u32x4*)m->lm_head_lo; p.NRG = m->V / 16; p.KB = d / 32;
+    p.X = (const u32x4*)m->xq; p.M = batch;
     p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
     p.logits = lg; p.V = m->V;
+    prof_mark(m, PK_LMHEAD, st);
     launch_gemm<EPI_LOGITS>(m, p, MT, st);
   }
+  if (next) prof_mark(m, PK_ARGMAX, st);
   if (next) hipLaunchKernelGGL(argmax_kernel, dim3(batch), dim3(1024), 0, st, lg, m->V, next);
+  prof_mark(m, -1, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     set_error("decode launch failed: %s", hipGetErrorString(e));

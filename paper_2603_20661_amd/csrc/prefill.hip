@@ -7,7 +7,7 @@
 
 #define NEG_INF (-__builtin_inff())
 
-__device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 #define ATTN_TQ 64  // query rows per attention workgroup
 
@@ -87,12 +87,12 @@ __global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restri
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
     float4 v = *reinterpret_cast<const float4*>(x + k);
     float4 g = *reinterpret_cast<const float4*>(gain + k);
-    union { uint16_t s[4]; uint2 v; } o;
+    union { uint16_t s[4]; u32x2 v; } o;
     o.s[0] = f32_to_f16_sat(v.x * rs * g.x);
     o.s[1] = f32_to_f16_sat(v.y * rs * g.y);
     o.s[2] = f32_to_f16_sat(v.z * rs * g.z);
     o.s[3] = f32_to_f16_sat(v.w * rs * g.w);
-    *reinterpret_cast<uint2*>(xn + r * d + k) = o.v;
+    *reinterpret_cast<u32x2*>(xn + r * d + k) = o.v;
   }
 }
 
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restri
 enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
 
 struct PGemmP {
-  const uint4* W;  // packed weights (hi plane)
+  const u32x4* W;  // packed weights (hi plane)
   int NRG, KB;
   const uint16_t* X;  // fp16 activations [T][ldx]
   int ldx, T;
@@ -126,7 +126,7 @@ struct PGemmP {
 
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
-  extern __shared__ uint4 smem[];  // [2][PG_STAGE_UNITS]
+  extern __shared__ u32x4 smem[];  // [2][PG_STAGE_UNITS]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
 
@@ -154,10 +154,9 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  uint4 sa[8], sb[8];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  u32x4 sa[8], sb[8];
 
-  auto load_stage = [&](int s) {
+  auto load_stage = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       int u = tid + i * 256;
@@ -165,23 +164,21 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         int frag = u >> 6, ln = u & 63;
         int rgl = frag >> 1, kbl = frag & 1;
         int rg = min(rg_tile + rgl, p.NRG - 1);
-        int kb = s * 2 + kbl;
-        bool ok = kb < p.KB;
-        uint4 w = p.W[((int64_t)rg * p.KB + (ok ? kb : p.KB - 1)) * 64 + ln];
-        sa[i] = ok ? w : zero4;
+        int kb = min(s * 2 + kbl, p.KB - 1);  // odd KB: the last stage's second half is skipped in compute()
+        sa[i] = p.W[((int64_t)rg * p.KB + kb) * 64 + ln];
       }
       {  // activations: token u / 8, 8 columns at (u % 8) * 8
         int tl = u >> 3, oct = u & 7;
         int t = min(t_tile + tl, p.T - 1);
         int k = s * 64 + oct * 8;
-        if (k >= p.KB * 32) k -= 32;  // odd KB: the second half of the last stage meets zero weights
-        sb[i] = *reinterpret_cast<const uint4*>(p.X + (int64_t)t * p.ldx + k);
+        if (k >= p.KB * 32) k -= 32;  // odd KB: in bounds, unused
+        sb[i] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)t * p.ldx + k);
       }
     }
   };
-  auto store_stage = [&](int buf) {
-    uint4* A = smem + buf * PG_STAGE_UNITS;
-    uint4* B = A + 2048;
+  auto store_stage = [&](int buf) __attribute__((always_inline)) {
+    u32x4* A = smem + buf * PG_STAGE_UNITS;
+    u32x4* B = A + 2048;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       int u = tid + i * 256;
@@ -191,12 +188,14 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
       B[(((tl >> 5) * 4 + (oct >> 1)) << 6) + (oct & 1) * 32 + (tl & 31)] = sb[i];
     }
   };
-  auto compute = [&](int buf) {
-    const uint4* A = smem + buf * PG_STAGE_UNITS;
-    const uint4* B = A + 2048;
+  auto compute = [&](int buf, int s) __attribute__((always_inline)) {
+    const u32x4* A = smem + buf * PG_STAGE_UNITS;
+    const u32x4* B = A + 2048;
     const int m = lane & 31, hh = lane >> 5;
+    const int nk16 = min(4, (p.KB - s * 2) * 2);  // 16-column steps of this stage inside K
 #pragma unroll
     for (int k16 = 0; k16 < 4; ++k16) {
+      if (k16 >= nk16) break;
       f16x8 af[4], bfr[4];
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
@@ -219,7 +218,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     const int buf = s & 1;
     const bool more = s + 1 < nstages;
     if (more) load_stage(s + 1);
-    compute(buf);
+    compute(buf, s);
     if (more) store_stage(buf ^ 1);
     __syncthreads();
   }
@@ -247,13 +246,13 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
         for (int q4 = 0; q4 < 2; ++q4) {
           int f0 = (rgb >> 1) * 16 + q4 * 8 + hsel * 4;
-          union { uint16_t s[4]; uint2 v; } o;
+          union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             float g = acc[rb][tb][q4 * 4 + i], u = acc[rb][tb][(q4 + 2) * 4 + i];
             o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
           }
-          *reinterpret_cast<uint2*>(p.ap + (int64_t)t * p.Fp + f0) = o.v;
+          *reinterpret_cast<u32x2*>(p.ap + (int64_t)t * p.Fp + f0) = o.v;
         }
       } else {
 #pragma unroll
@@ -280,14 +279,14 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
                 v4[2 * pr + 1] = b * cs.x + a * cs.y;
               }
             }
-            union { uint16_t s[4]; uint2 v; } o;
+            union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(v4[i]);  // q, k, v feed the fp16 attention kernels
             if (head < p.Hq) {
-              *reinterpret_cast<uint2*>(p.qp + (int64_t)t * (p.Hq * p.hd) + n0) = o.v;
+              *reinterpret_cast<u32x2*>(p.qp + (int64_t)t * (p.Hq * p.hd) + n0) = o.v;
             } else if (head < p.Hq + p.Hkv) {
               const int j = head - p.Hq;
-              *reinterpret_cast<uint2*>(p.kplane + (kvbase + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = o.v;
+              *reinterpret_cast<u32x2*>(p.kplane + (kvbase + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = o.v;
             } else {
               const int j = head - p.Hq - p.Hkv;
               uint16_t* dst = p.vplane + (kvbase + j) * (int64_t)(KV_BS * p.hd);
@@ -340,7 +339,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
   for (int hh = 0; hh < GH; ++hh)
 #pragma unroll
     for (int f = 0; f < NKF; ++f)
-      qf[hh][f] = as_f16x8(*reinterpret_cast<const uint4*>(qp + (row0 + my_q) * QD + (h0 + hh) * HD + f * 32 + g * 8));
+      qf[hh][f] = as_f16x8(*reinterpret_cast<const u32x4*>(qp + (row0 + my_q) * QD + (h0 + hh) * HD + f * 32 + g * 8));
 
   f32x4 oacc[GH][NVF];
   float m_run[GH], l_run[GH];
@@ -359,17 +358,17 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
     const int bi1 = min(bi0 + 1, last_blk);
     const int64_t off0 = ((int64_t)trow[bi0] * Hkv + j) * blk_elems;
     const int64_t off1 = ((int64_t)trow[bi1] * Hkv + j) * blk_elems;
-    uint4 kf0[NKF], kf1[NKF];
-    uint2 vf0[NVF], vf1[NVF];
+    u32x4 kf0[NKF], kf1[NKF];
+    u32x2 vf0[NVF], vf1[NVF];
 #pragma unroll
     for (int f = 0; f < NKF; ++f) {
-      kf0[f] = *reinterpret_cast<const uint4*>(kplane + off0 + (f * 64 + lane) * 8);
-      kf1[f] = *reinterpret_cast<const uint4*>(kplane + off1 + (f * 64 + lane) * 8);
+      kf0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
+      kf1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      vf0[f] = *reinterpret_cast<const uint2*>(vplane + off0 + (f * 64 + lane) * 4);
-      vf1[f] = *reinterpret_cast<const uint2*>(vplane + off1 + (f * 64 + lane) * 4);
+      vf0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
+      vf1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
     }
     if (base + 32 > ctx) {  // slots past the end of the sequence may hold anything: keep them out of the MFMA
       const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
@@ -417,7 +416,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
       m_run[hh] = m_new;
 #pragma unroll
       for (int f = 0; f < NVF; ++f) {
-        uint4 a = make_uint4(vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y);
+        u32x4 a = {vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y};
         oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
         oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[hh][f], 0, 0, 0);
       }
@@ -432,10 +431,10 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
     const float inv = 1.f / l;
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      union { uint16_t s[4]; uint2 v; } o;
+      union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
       for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(oacc[hh][f][i] * inv);
-      *reinterpret_cast<uint2*>(op + (row0 + n) * QD + (h0 + hh) * HD + f * 16 + g * 4) = o.v;
+      *reinterpret_cast<u32x2*>(op + (row0 + n) * QD + (h0 + hh) * HD + f * 16 + g * 4) = o.v;
     }
   }
 }
@@ -496,7 +495,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.attn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
-      p.W = (const uint4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       launch_pgemm<PEPI_QKV>(p, st);
@@ -506,20 +505,20 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     else launch_pattn<64>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
     {
       PGemmP p = {};
-      p.W = (const uint4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const uint16_t*)m->op; p.ldx = m->QD; p.T = T;
+      p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const uint16_t*)m->op; p.ldx = m->QD; p.T = T;
       p.hp = m->hp; p.d = d;
       launch_pgemm<PEPI_RESID>(p, st);
     }
     hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.ffn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
-      p.W = (const uint4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
       p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
       launch_pgemm<PEPI_SWIGLU>(p, st);
     }
     {
       PGemmP p = {};
-      p.W = (const uint4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const uint16_t*)m->ap; p.ldx = m->Fp; p.T = T;
+      p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const uint16_t*)m->ap; p.ldx = m->Fp; p.T = T;
       p.hp = m->hp; p.d = d;
       launch_pgemm<PEPI_RESID>(p, st);
     }

@@ -1,0 +1,54 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header
+declares, and validates configurations and arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_20661_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+B = pytest.importorskip("paper_2603_20661_amd.binding", reason="libwww.so is not built")
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "www.h")).read()
+    declared = set(re.findall(r"\b(www_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+def test_config_struct_matches_header_layout():
+    assert ctypes.sizeof(B.WwwConfig) == 18 * 4
+    assert B.WwwConfig.num_kv_blocks.offset == 64
+
+
+def test_query_sizes_and_config_validation():
+    cfg = B.make_config(synth.M8B, 64, 272, 81920, 6000)
+    wbytes, kvbytes, wsbytes = B.www_query_sizes(cfg)
+    assert wbytes == synth.blob_layout(synth.M8B)[1]
+    assert kvbytes == 6000 * 32 * 2 * 8 * 16 * 128 * 2          # 2 MiB per block for the 8B shape
+    assert wsbytes > synth.M8B.n_params() * 2 - synth.M8B.vocab * synth.M8B.d_model * 2
+    for field, value, code in (("abi_version", 99, B.E_ABI_MISMATCH), ("head_dim", 96, B.E_BAD_CONFIG),
+                               ("kv_block_size", 32, B.E_BAD_CONFIG), ("n_kv_heads", 3, B.E_BAD_CONFIG),
+                               ("vocab", 1001, B.E_BAD_CONFIG), ("max_batch", 0, B.E_BAD_CONFIG), ("reserved", 1, B.E_BAD_CONFIG)):
+        bad = B.make_config(synth.TINY, 4, 16, 512, 64)
+        setattr(bad, field, value)
+        with pytest.raises(B.WwwError) as e:
+            B.www_query_sizes(bad)
+        assert e.value.code == code and str(e.value)
+
+
+def test_null_arguments_are_rejected_before_any_launch():
+    assert B.lib.www_query_sizes(None, None, None, None) == B.E_INVALID_ARG
+    cfg = B.make_config(synth.TINY, 4, 16, 512, 64)
+    h = ctypes.c_void_p()
+    assert B.lib.www_model_load(ctypes.byref(cfg), None, None, None, None, ctypes.byref(h)) == B.E_INVALID_ARG
+    assert B.lib.www_model_load(ctypes.byref(cfg), 256, 512, 100, None, ctypes.byref(h)) == B.E_INVALID_ARG   # misaligned workspace
+    assert B.lib.www_prefill(None, None, None, None, None, 1, 1, None, None, None) == B.E_INVALID_ARG
+    assert B.lib.www_decode_step(None, None, None, None, 1, None, None, None) == B.E_INVALID_ARG
+    assert B.lib.www_debug_slots(None, None, 1, None, None) == B.E_INVALID_ARG
+    assert b"NULL" in B.lib.www_last_error() or b"bad" in B.lib.www_last_error()
+    B.lib.www_model_free(None)
