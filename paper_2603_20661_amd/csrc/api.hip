@@ -147,7 +147,7 @@ static void make_plan(const www_config* c, Plan& p) {
     for (int i = 0; i < 5; ++i)
       for (int mt = 1; mt <= s.MTmax; mt = mt < 4 ? mt * 2 : mt + 4) {  // every token-group count a batch can produce
         uint64_t ks = decode_gemm_ksplit(N[i] / 16, K[i] / 32, mt);
-        uint64_t bytes = ks * mt * 16 * N[i] * 4;
+        uint64_t bytes = ks * mt * 16 * (((uint64_t)N[i] + 127) / 128 * 128) * 4;  // whole 128-row tiles are parked
         if (ks > 1 && bytes > part) part = bytes;
       }
   }

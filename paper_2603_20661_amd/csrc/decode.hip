@@ -30,15 +30,15 @@ __device__ __forceinline__ float ssq_total(const float* __restrict__ ssq, int n_
 // XCD's write-back L2; the producer waits for its stores to complete, the workgroup syncs, and one thread bumps a
 // device-scope counter.  This avoids device-scope fences, whose whole-L2 write-back / invalidate costs tens of
 // microseconds per kernel here.
-__device__ __forceinline__ void store_shared_f32x4(float* p, f32x4 v) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// 16-byte accesses with device scope (cache-policy bit 4 = sc1 on gfx942/gfx950) through a raw buffer descriptor
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t shared_rsrc(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
 }
-__device__ __forceinline__ f32x4 load_shared_f32x4(const float* p) {
-  f32x4 v;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return v;
+__device__ __forceinline__ void store_shared_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, 16);
+}
+__device__ __forceinline__ f32x4 load_shared_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 16));
 }
 __device__ __forceinline__ void store_shared_f32(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float load_shared_f32(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -261,21 +261,21 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   }
 
   // accumulator layout: acc[r][tb][i] = Y^T[row][token], row = (rg0+r)*16 + (lane/16)*4 + i, token = (tb0+tb)*16 + lane%16
-  const int Npad = p.NRG * 16;
   const int rsub = (lane >> 4) * 4;
   const int tsub = lane & 15;
 
   if (p.ksplit > 1) {
     // split-K: park the partial tile, and let the workgroup that arrives last add all partial tiles in split order
+    // parked as a register image: unit ((((split, zb, tile), wave), r), tb), lane -> one 16-byte store per lane,
+    // 1 KiB contiguous per instruction; the last workgroup reads it back with the same thread mapping
+    const __amdgpu_buffer_rsrc_t prs = shared_rsrc(p.partial);
+    auto punit = [&](int sp, int r, int tb) __attribute__((always_inline)) {
+      return (uint32_t)((((((sp * (int)gridDim.z + zb) * (int)gridDim.x + tile) * 4 + wave) * R + r) * MTK + tb) * 64 + lane) * 16u;
+    };
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (rg0 + r >= p.NRG) continue;
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int tb = 0; tb < MTK; ++tb) {
-        int t = (tb0 + tb) * 16 + tsub;
-        store_shared_f32x4(p.partial + ((int64_t)split * (p.MT * 16) + t) * Npad + (rg0 + r) * 16 + rsub, acc[r][tb]);
-      }
-    }
+      for (int tb = 0; tb < MTK; ++tb) store_shared_f32x4(prs, punit(split, r, tb), acc[r][tb]);
     wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
@@ -299,11 +299,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int tb = 0; tb < MTK; ++tb) {
-            const int t = (tb0 + tb) * 16 + tsub;
-            const int rgs = min(rg0 + r, p.NRG - 1);
-            pv[u][r][tb] = load_shared_f32x4(p.partial + ((int64_t)sidx * (p.MT * 16) + t) * Npad + rgs * 16 + rsub);
-          }
+          for (int tb = 0; tb < MTK; ++tb) pv[u][r][tb] = load_shared_f32x4(prs, punit(sidx, r, tb));
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -559,10 +555,11 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
 
   // park this split's record: [b][j][split][head n][o(HD), m, l]
   float* rec = part + ((((int64_t)b * Hkv + j) * nsplit_max + split) * G) * PSTRIDE;
+  const __amdgpu_buffer_rsrc_t part_rs = shared_rsrc(part);
   if (n < G) {
 #pragma unroll
     for (int f = 0; f < NVF; ++f)
-      store_shared_f32x4(rec + n * PSTRIDE + f * 16 + g * 4, oacc[f]);
+      store_shared_f32x4(part_rs, (uint32_t)((rec - part) + n * PSTRIDE + f * 16 + g * 4) * 4u, oacc[f]);
     if (g == 0) {
       store_shared_f32(rec + n * PSTRIDE + HD, m_run);
       store_shared_f32(rec + n * PSTRIDE + HD + 1, l_run);
