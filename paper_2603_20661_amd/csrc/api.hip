@@ -158,10 +158,11 @@ static void make_plan(const www_config* c, Plan& p) {
   p.logits = take((uint64_t)s.maxB * s.V * 4);
   p.last_tok = take((uint64_t)s.maxB * 4);
   p.hp = take((uint64_t)s.maxT * s.d * 4);
-  p.xn = take((uint64_t)s.maxT * s.d * 2);
+  const uint64_t Tpad = ((uint64_t)s.maxT + 255) / 256 * 256;  // packed activation buffers hold whole 256-token tiles
+  p.xn = take(Tpad * s.d * 2);
   p.qp = take((uint64_t)s.maxT * s.QD * 2);
-  p.op = take((uint64_t)s.maxT * s.QD * 2);
-  p.ap = take((uint64_t)s.maxT * s.Fp * 2);
+  p.op = take(Tpad * s.QD * 2);
+  p.ap = take(Tpad * s.Fp * 2);
   p.row_seq = take((uint64_t)s.maxT * 4);
   p.row_pos = take((uint64_t)s.maxT * 4);
   const uint64_t max_tiles = (uint64_t)s.maxT / 64 + s.maxB + 1;

@@ -36,6 +36,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 //   lane l holds token tb*16 + l%16, columns kb*32 + (l/16)*8 .. +7; x = hi + lo with hi = fp16(x).
 //   element offset = (((kb*MT + tb)*2 + hl)*64 + l)*8 + e.
 //
+// Packed activations X[T][K] for the prefill path (fp16, no hi/lo), tokens in groups of 32, columns in steps of 16:
+//   fragment (tb, ks) = tokens tb*32..+31, columns ks*16..+15 = B operand of the 32x32x16 MFMA:
+//   lane l holds token tb*32 + l%32, columns ks*16 + (l/32)*8 .. +7;  element offset = ((tb*(K/16) + ks)*64 + l)*8 + e.
+//   Buffers are sized for the token count rounded up to 256.
+//
 // KV pool: [layer][K|V][block][kv head][16 tokens x hd]; inside one (block, head):
 //   K (head-dim in rotary-interleaved order c): offset = ((c/32)*64 + ((c%32)/8)*16 + tok)*8 + c%8
 //        -> fragment c/32 is the A operand of S^T = K Q^T for those 32 dims.
@@ -57,6 +62,10 @@ __device__ __forceinline__ float f16_bits_to_float(uint16_t h) { return (float)_
 __device__ __forceinline__ void split_f16(float x, uint16_t& hi, uint16_t& lo) {
   hi = f32_to_f16_sat(x);
   lo = f32_to_f16_sat(x - f16_bits_to_float(hi));
+}
+
+__device__ __forceinline__ int64_t packed_p_offset(int64_t t, int k, int K16) {
+  return (((t >> 5) * K16 + (k >> 4)) * 64 + ((k & 15) >> 3) * 32 + (t & 31)) * 8 + (k & 7);
 }
 
 __device__ __forceinline__ int k_cache_offset(int tok, int c) { return ((c >> 5) * 64 + ((c & 31) >> 3) * 16 + tok) * 8 + (c & 7); }
@@ -107,10 +116,10 @@ struct www_model {
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
   // prefill-path buffers
   float* hp;       // [maxT][d]
-  uint16_t* xn;        // [maxT][d] normalised activations
+  uint16_t* xn;        // packed [maxT][d] normalised activations
   uint16_t* qp;    // [maxT][QD] rotated queries, fp16 (interleaved head-dim order)
-  uint16_t* op;        // [maxT][QD] attention output
-  uint16_t* ap;        // [maxT][Fp] SwiGLU output
+  uint16_t* op;        // packed [maxT][QD] attention output
+  uint16_t* ap;        // packed [maxT][Fp] SwiGLU output
   int *row_seq, *row_pos, *tile_seq, *tile_q0, *meta;  // ragged-batch bookkeeping
   int attn_kps;    // keys per decode-attention split
   int attn_splits; // grid.x of the decode attention

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
   }
 }
 
-// xn[r] = fp16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain )
+// xn[r] = fp16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ), written in the packed prefill layout
 __global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restrict__ hp, const float* __restrict__ gain, int d, float eps,
                                                             uint16_t* __restrict__ xn) {
   int64_t r = blockIdx.x;
@@ -92,21 +92,22 @@ __global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restri
     o.s[1] = f32_to_f16_sat(v.y * rs * g.y);
     o.s[2] = f32_to_f16_sat(v.z * rs * g.z);
     o.s[3] = f32_to_f16_sat(v.w * rs * g.w);
-    *reinterpret_cast<u32x2*>(xn + r * d + k) = o.v;
+    *reinterpret_cast<u32x2*>(xn + packed_p_offset(r, k, d >> 4)) = o.v;
   }
 }
 
 // ------------------------------------------------------------------------------------------------
 // Tiled GEMM  Y^T[n][t] = sum_k W[n][k] X[t][k]:  256 weight rows x 256 tokens per workgroup, four
-// wavefronts each owning 128 x 128 as 4 x 4 MFMA 32x32x16 tiles, K in steps of 64 through
-// double-buffered LDS.
+// wavefronts each owning 128 x 128 as 4 x 4 MFMA 32x32x16 tiles.  Both operands arrive already in MFMA
+// fragment order (packed weights, packed activations), so a K step of 32 is a straight 32 KiB copy into
+// LDS (16 weight fragments + 16 activation fragments) and every LDS read is a conflict-free 16-byte read.
 enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
 
 struct PGemmP {
-  const u32x4* W;  // packed weights (hi plane)
+  const u32x4* W;  // packed weights
   int NRG, KB;
-  const uint16_t* X;  // fp16 activations [T][ldx]
-  int ldx, T;
+  const u32x4* X;  // packed activations
+  int T;
   int n_tt, n_rt;  // token tiles, row tiles
   // QKV epilogue
   uint16_t* qp;
@@ -122,11 +123,9 @@ struct PGemmP {
   int Fp;
 };
 
-#define PG_STAGE_UNITS 4096  // 16-byte units per stage: 2048 of W + 2048 of X
-
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
-  extern __shared__ u32x4 smem[];  // [2][PG_STAGE_UNITS]
+  __shared__ u32x4 smem[2][2048];  // per stage: units 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
 
@@ -144,7 +143,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 
   const int rg_tile = rt * 16;
   const int t_tile = tt * 256;
-  const int nstages = (p.KB + 1) / 2;
+  const int K16 = p.KB * 2;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -154,56 +153,41 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  u32x4 sa[8], sb[8];
-
-  auto load_stage = [&](int s) __attribute__((always_inline)) {
+  // global source of this thread's 4 + 4 staging units (they advance by one k block per stage)
+  const u32x4* srcA[4];
+  const u32x4* srcB[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int u = tid + i * 256;
-      {  // weights: fragment (rgl, kbl), lane u % 64
-        int frag = u >> 6, ln = u & 63;
-        int rgl = frag >> 1, kbl = frag & 1;
-        int rg = min(rg_tile + rgl, p.NRG - 1);
-        int kb = min(s * 2 + kbl, p.KB - 1);  // odd KB: the last stage's second half is skipped in compute()
-        sa[i] = p.W[((int64_t)rg * p.KB + kb) * 64 + ln];
-      }
-      {  // activations: token u / 8, 8 columns at (u % 8) * 8
-        int tl = u >> 3, oct = u & 7;
-        int t = min(t_tile + tl, p.T - 1);
-        int k = s * 64 + oct * 8;
-        if (k >= p.KB * 32) k -= 32;  // odd KB: in bounds, unused
-        sb[i] = *reinterpret_cast<const u32x4*>(p.X + (int64_t)t * p.ldx + k);
-      }
+  for (int i = 0; i < 4; ++i) {
+    const int f = wave + 4 * i;  // fragment 0..15 handled by this wavefront
+    srcA[i] = p.W + ((int64_t)min(rg_tile + f, p.NRG - 1) * p.KB) * 64 + lane;
+    srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64 + lane;
+  }
+  u32x4 sa[4], sb[4];
+  auto load_stage = [&](int kb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      sa[i] = srcA[i][(int64_t)kb * 64];
+      sb[i] = srcB[i][(int64_t)kb * 128];
     }
   };
   auto store_stage = [&](int buf) __attribute__((always_inline)) {
-    u32x4* A = smem + buf * PG_STAGE_UNITS;
-    u32x4* B = A + 2048;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int u = tid + i * 256;
-      A[u] = sa[i];
-      int tl = u >> 3, oct = u & 7;
-      // B operand of the 32x32x16 MFMA: block of 32 tokens, 16-column step, lane = (oct & 1) * 32 + token % 32
-      B[(((tl >> 5) * 4 + (oct >> 1)) << 6) + (oct & 1) * 32 + (tl & 31)] = sb[i];
+    for (int i = 0; i < 4; ++i) {
+      smem[buf][(wave + 4 * i) * 64 + lane] = sa[i];
+      smem[buf][1024 + (wave + 4 * i) * 64 + lane] = sb[i];
     }
   };
-  auto compute = [&](int buf, int s) __attribute__((always_inline)) {
-    const u32x4* A = smem + buf * PG_STAGE_UNITS;
-    const u32x4* B = A + 2048;
+  auto compute = [&](int buf) __attribute__((always_inline)) {
+    const u32x4* A = smem[buf];
+    const u32x4* B = smem[buf] + 1024;
     const int m = lane & 31, hh = lane >> 5;
-    const int nk16 = min(4, (p.KB - s * 2) * 2);  // 16-column steps of this stage inside K
 #pragma unroll
-    for (int k16 = 0; k16 < 4; ++k16) {
-      if (k16 >= nk16) break;
+    for (int k16 = 0; k16 < 2; ++k16) {
       f16x8 af[4], bfr[4];
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        int rgl = wn * 8 + rb * 2 + (m >> 4);
-        af[rb] = as_f16x8(A[((rgl * 2 + (k16 >> 1)) << 6) + (((k16 & 1) * 2 + hh) << 4) + (m & 15)]);
-      }
+      for (int rb = 0; rb < 4; ++rb) af[rb] = as_f16x8(A[(wn * 8 + rb * 2 + (m >> 4)) * 64 + ((k16 * 2 + hh) << 4) + (m & 15)]);
 #pragma unroll
-      for (int tb = 0; tb < 4; ++tb) bfr[tb] = as_f16x8(B[(((wt * 4 + tb) * 4 + k16) << 6) + lane]);
+      for (int tb = 0; tb < 4; ++tb) bfr[tb] = as_f16x8(B[((wt * 4 + tb) * 2 + k16) * 64 + lane]);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
@@ -211,17 +195,19 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     }
   };
 
+  // software pipeline over k blocks: the loads of block s+1 are in flight while block s is multiplied
   load_stage(0);
   store_stage(0);
   __syncthreads();
-  for (int s = 0; s < nstages; ++s) {
-    const int buf = s & 1;
-    const bool more = s + 1 < nstages;
-    if (more) load_stage(s + 1);
-    compute(buf, s);
-    if (more) store_stage(buf ^ 1);
+  for (int s = 0; s + 1 < p.KB; ++s) {
+    load_stage(s + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(s & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    store_stage((s + 1) & 1);
     __syncthreads();
   }
+  compute((p.KB - 1) & 1);
 
   // acc[rb][tb][i] = Y^T[row][token]: row = (rg_tile + wn*8 + rb*2)*16 + (i/4)*8 + (lane/32)*4 + i%4, token = t_tile + wt*128 + tb*32 + lane%32
   const int hsel = lane >> 5;
@@ -252,7 +238,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
             float g = acc[rb][tb][q4 * 4 + i], u = acc[rb][tb][(q4 + 2) * 4 + i];
             o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
           }
-          *reinterpret_cast<u32x2*>(p.ap + (int64_t)t * p.Fp + f0) = o.v;
+          *reinterpret_cast<u32x2*>(p.ap + packed_p_offset(t, f0, p.Fp >> 4)) = o.v;
         }
       } else {
 #pragma unroll
@@ -434,7 +420,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
       union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
       for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(oacc[hh][f][i] * inv);
-      *reinterpret_cast<u32x2*>(op + (row0 + n) * QD + (h0 + hh) * HD + f * 16 + g * 4) = o.v;
+      *reinterpret_cast<u32x2*>(op + packed_p_offset(row0 + n, (h0 + hh) * HD + f * 16 + g * 4, QD >> 4)) = o.v;
     }
   }
 }
@@ -442,22 +428,11 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
 // ------------------------------------------------------------------------------------------------
 // Host side
 
-static bool g_attr_set = false;
-static void set_smem_attrs() {
-  if (g_attr_set) return;
-  const int bytes = 2 * PG_STAGE_UNITS * 16;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_QKV>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_gemm_kernel<PEPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  g_attr_set = true;
-}
-
 template <int EPI>
 static void launch_pgemm(PGemmP& p, hipStream_t st) {
   p.n_tt = (p.T + 255) / 256;
   p.n_rt = (p.NRG + 15) / 16;
-  const int bytes = 2 * PG_STAGE_UNITS * 16;
-  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), bytes, st, p);
+  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), 0, st, p);
 }
 
 template <int HD>
@@ -478,7 +453,6 @@ static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* v
 
 int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const int32_t* lens, const int32_t* table, int batch, int T,
                 hipStream_t st) {
-  set_smem_attrs();
   const int d = m->d;
   int32_t* cum = m->meta + 16;
   hipLaunchKernelGGL(prefill_meta_kernel, dim3(1), dim3(1024), 0, st, tok, qlens, lens, batch, T, m->row_seq, m->row_pos, m->tile_seq,
@@ -495,7 +469,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.attn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       launch_pgemm<PEPI_QKV>(p, st);
@@ -505,20 +479,20 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     else launch_pattn<64>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const uint16_t*)m->op; p.ldx = m->QD; p.T = T;
+      p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;
       p.hp = m->hp; p.d = d;
       launch_pgemm<PEPI_RESID>(p, st);
     }
     hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.ffn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const uint16_t*)m->xn; p.ldx = d; p.T = T;
+      p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
       launch_pgemm<PEPI_SWIGLU>(p, st);
     }
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const uint16_t*)m->ap; p.ldx = m->Fp; p.T = T;
+      p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
       p.hp = m->hp; p.d = d;
       launch_pgemm<PEPI_RESID>(p, st);
     }
