@@ -26,7 +26,9 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 // Packed weight matrix W[N][K] (out x in), K padded with zeros to KB*32:
 //   fragment (rg, kb) = rows rg*16..+15, columns kb*32..+31, 1 KiB, stored lane-major for the
 //   16x16x32 MFMA A operand: lane l holds row rg*16 + l%16, columns kb*32 + (l/16)*8 .. +7.
-//   element offset = ((rg*KB + kb)*64 + l)*8 + e.
+//   Fragments are ordered k block first: element offset = ((kb*NRG + rg)*64 + l)*8 + e (NRG = N/16), so the
+//   workgroups of a GEMM, which walk K in step, read one contiguous region per k block - no HBM channel sees a
+//   power-of-two stride.
 //   Rows may be permuted at pack time (packed row p <-> source row, see pack.hip):
 //     QKV: inside each q and k head, p = 2i -> i, p = 2i+1 -> i + hd/2  (rotary pairs adjacent)
 //     gate/up: row-group 2j = gate rows 16j..16j+15, row-group 2j+1 = up rows 16j..16j+15

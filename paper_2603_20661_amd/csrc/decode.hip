@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
       const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        const int64_t idx = ((int64_t)rgc[r] * p.KB + kbc) * 64 + lane;
+        const int64_t idx = ((int64_t)kbc * p.NRG + rgc[r]) * 64 + lane;
         w[kk][r][0] = p.W[idx];
         if constexpr (WSPLIT) w[kk][r][1] = p.Wlo[idx];
       }
@@ -199,15 +199,26 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 #pragma unroll
     for (int i = 0; i < NSTG; ++i) lds[buf][tid + i * 256] = stg[i];
   };
-  // nvalid = k blocks of the chunk that lie inside the range: KC for every chunk but possibly the last
+  // nvalid = k blocks of the chunk that lie inside the range: KC for every chunk but possibly the last.
+  // The B fragments (activations) of k block kk+1 are fetched from LDS while the MFMAs of k block kk run.
   auto compute = [&](u32x4(&w)[KC][R][WP], int buf, int nvalid) __attribute__((always_inline)) {
+    u32x4 bq[2][MTK][2];
+    auto fetch = [&](int set, int kk) __attribute__((always_inline)) {
+#pragma unroll
+      for (int tb = 0; tb < MTK; ++tb) {
+        bq[set][tb][0] = lds[buf][(kk * MTK + tb) * 128 + lane];
+        bq[set][tb][1] = lds[buf][(kk * MTK + tb) * 128 + 64 + lane];
+      }
+    };
+    fetch(0, 0);
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
       if (kk >= nvalid) break;
+      if (kk + 1 < KC) fetch((kk + 1) & 1, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
-        f16x8 bhi = as_f16x8(lds[buf][(kk * MTK + tb) * 128 + lane]);
-        f16x8 blo = as_f16x8(lds[buf][(kk * MTK + tb) * 128 + 64 + lane]);
+        const f16x8 bhi = as_f16x8(bq[kk & 1][tb][0]), blo = as_f16x8(bq[kk & 1][tb][1]);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           f16x8 a = as_f16x8(w[kk][r][0]);
@@ -216,6 +227,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
           if constexpr (WSPLIT) acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(w[kk][r][1]), bhi, acc[r][tb], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -464,32 +476,40 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
   float m_run = NEG_INF, l_run = 0.f;
 
   const int64_t blk_elems = (int64_t)KV_BS * HD;
-  for (int pr = 0; pr < npairs; ++pr) {
-    const int base = k0 + pr * 32;
-    const int bi0 = base / KV_BS;
-    const int bi1 = min(bi0 + 1, last_blk);
-    const int64_t off0 = ((int64_t)trow[bi0] * Hkv + j) * blk_elems;
-    const int64_t off1 = ((int64_t)trow[bi1] * Hkv + j) * blk_elems;
-    u32x4 kf0[NKF], kf1[NKF];
-    u32x2 vf0[NVF], vf1[NVF];
+  // physical ids of this split's blocks, one per lane, fetched once (a split spans at most 64 blocks)
+  const int blk0 = k0 / KV_BS;
+  const int my_blk = trow[min(blk0 + lane, last_blk)];
+
+  struct KV {
+    u32x4 k0[NKF], k1[NKF];
+    u32x2 v0[NVF], v1[NVF];
+  };
+  auto load_pair = [&](KV& r, int pr) __attribute__((always_inline)) {
+    const int id0 = __builtin_amdgcn_readlane(my_blk, min(2 * pr, 63));
+    const int id1 = __builtin_amdgcn_readlane(my_blk, min(2 * pr + 1, 63));  // past the sequence end this repeats the last block (masked)
+    const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
+    const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
 #pragma unroll
     for (int f = 0; f < NKF; ++f) {
-      kf0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
-      kf1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
+      r.k0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
+      r.k1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      vf0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
-      vf1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
+      r.v0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
+      r.v1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
     }
+  };
+  auto process = [&](KV& r, int pr) __attribute__((always_inline)) {
+    const int base = k0 + pr * 32;
     // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1)
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int f = 0; f < NKF; ++f) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qhi[f], s0, 0, 0, 0);
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qlo[f], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qhi[f], s1, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qlo[f], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qhi[f], s0, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qlo[f], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qhi[f], s1, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qlo[f], s1, 0, 0, 0);
     }
     float sc[8];
     float mx = NEG_INF;
@@ -522,17 +542,40 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
       const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
 #pragma unroll
       for (int f = 0; f < NVF; ++f) {
-        vf0[f].x &= a01; vf0[f].y &= a23;
-        vf1[f].x &= b01; vf1[f].y &= b23;
+        r.v0[f].x &= a01; r.v0[f].y &= a23;
+        r.v1[f].x &= b01; r.v1[f].y &= b23;
       }
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      u32x4 a = {vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y};
+      u32x4 a = {r.v0[f].x, r.v0[f].y, r.v1[f].x, r.v1[f].y};
       oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
       oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
     }
+  };
+
+  // two register sets: the keys and values of pair pr+1 travel while pair pr is processed
+  KV ra, rb;
+  load_pair(ra, 0);
+  int pr = 0;
+  bool done = false;
+  while (pr + 1 < npairs) {
+    load_pair(rb, pr + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    process(ra, pr);
+    ++pr;
+    if (pr + 1 >= npairs) {
+      process(rb, pr);
+      done = true;
+      break;
+    }
+    load_pair(ra, pr + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    process(rb, pr);
+    ++pr;
   }
+  if (!done) process(ra, pr);
+
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
 
@@ -695,11 +738,11 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.partial = m->partial;
   p.counters = m->counters;
   dim3 grid(row_tiles, p.ksplit, zb), block(256);
-#define LAUNCH(MTK_, WS_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WS_, EPI>), grid, block, 0, st, p)
+#define LAUNCH(MTK_, WS_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WS_, EPI>), grid, block, 0, st, p);
   if (m->wsplit) {
-    if (mtk == 1) LAUNCH(1, true); else if (mtk == 2) LAUNCH(2, true); else LAUNCH(4, true);
+    if (mtk == 1) LAUNCH(1, true) else if (mtk == 2) LAUNCH(2, true) else LAUNCH(4, true)
   } else {
-    if (mtk == 1) LAUNCH(1, false); else if (mtk == 2) LAUNCH(2, false); else LAUNCH(4, false);
+    if (mtk == 1) LAUNCH(1, false) else if (mtk == 2) LAUNCH(2, false) else LAUNCH(4, false)
   }
 #undef LAUNCH
 }

@@ -25,8 +25,9 @@ __global__ void pack_matrix_kernel(const SRC* __restrict__ src, int N, int K, in
   if (idx >= total) return;
   int lane = (int)(idx & 63);
   int64_t frag = idx >> 6;
-  int kb = (int)(frag % KB);
-  int rg = (int)(frag / KB);
+  const int NRG = N / 16;
+  int rg = (int)(frag % NRG);
+  int kb = (int)(frag / NRG);
   int p = rg * 16 + (lane & 15);
   int k0 = kb * 32 + (lane >> 4) * 8;
   int64_t srow = source_row(p, mode, hd, n_rot_rows, F);

@@ -159,14 +159,14 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int f = wave + 4 * i;  // fragment 0..15 handled by this wavefront
-    srcA[i] = p.W + ((int64_t)min(rg_tile + f, p.NRG - 1) * p.KB) * 64 + lane;
+    srcA[i] = p.W + (int64_t)min(rg_tile + f, p.NRG - 1) * 64 + lane;
     srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64 + lane;
   }
   u32x4 sa[4], sb[4];
   auto load_stage = [&](int kb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      sa[i] = srcA[i][(int64_t)kb * 64];
+      sa[i] = srcA[i][(int64_t)kb * p.NRG * 64];
       sb[i] = srcB[i][(int64_t)kb * 128];
     }
   };
