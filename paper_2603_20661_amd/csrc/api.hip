@@ -89,7 +89,7 @@ struct Plan {
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
   uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok;
-  uint64_t hp, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
+  uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
   int attn_kps, attn_splits;
 };
 
@@ -159,6 +159,7 @@ static void make_plan(const www_config* c, Plan& p) {
   p.last_tok = take((uint64_t)s.maxB * 4);
   p.hp = take((uint64_t)s.maxT * s.d * 4);
   const uint64_t Tpad = ((uint64_t)s.maxT + 255) / 256 * 256;  // packed activation buffers hold whole 256-token tiles
+  p.ssq_p = take(Tpad * ((uint64_t)s.d / 256 + 1) * 4);
   p.xn = take(Tpad * s.d * 2);
   p.qp = take((uint64_t)s.maxT * s.QD * 2);
   p.op = take(Tpad * s.QD * 2);
@@ -285,7 +286,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
   m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
   m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
-  m->hp = (float*)(ws + p.hp); m->xn = (uint16_t*)(ws + p.xn); m->qp = (uint16_t*)(ws + p.qp); m->op = (uint16_t*)(ws + p.op); m->ap = (uint16_t*)(ws + p.ap);
+  m->hp = (float*)(ws + p.hp); m->ssq_p = (float*)(ws + p.ssq_p); m->xn = (uint16_t*)(ws + p.xn); m->qp = (uint16_t*)(ws + p.qp); m->op = (uint16_t*)(ws + p.op); m->ap = (uint16_t*)(ws + p.ap);
   m->row_seq = (int*)(ws + p.row_seq); m->row_pos = (int*)(ws + p.row_pos); m->tile_seq = (int*)(ws + p.tile_seq);
   m->tile_q0 = (int*)(ws + p.tile_q0); m->meta = (int*)(ws + p.meta);
   m->attn_kps = p.attn_kps; m->attn_splits = p.attn_splits;
@@ -296,11 +297,12 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
 WWW_EXPORT int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
                            const int32_t* block_table_dev, int32_t batch, int32_t total_q_tokens, float* logits_dev,
                            int32_t* next_tokens_dev, void* hip_stream) {
-  if (!m || !tokens_dev || !q_lens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
   if (batch < 0 || total_q_tokens < 0 || total_q_tokens < batch) { set_error("bad batch / total_q_tokens"); return WWW_E_INVALID_ARG; }
+  if (batch == 0) return WWW_OK;  // nothing to do; the pointers of empty arrays may be NULL
+  if (!tokens_dev || !q_lens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
   if (total_q_tokens > m->maxT) { set_error("total_q_tokens %d exceeds max_prefill_tokens %d", total_q_tokens, m->maxT); return WWW_E_CAPACITY; }
-  if (batch == 0) return WWW_OK;
   hipStream_t st = (hipStream_t)hip_stream;
   int rc = run_prefill(m, tokens_dev, q_lens_dev, seq_lens_dev, block_table_dev, batch, total_q_tokens, st);
   if (rc) return rc;
@@ -310,10 +312,11 @@ WWW_EXPORT int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_
 
 WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
                                int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream) {
-  if (!m || !last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
+  if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
   if (batch < 0) { set_error("negative batch"); return WWW_E_INVALID_ARG; }
+  if (batch == 0) return WWW_OK;  // nothing to do; the pointers of empty arrays may be NULL
+  if (!last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
-  if (batch == 0) return WWW_OK;
   hipStream_t st = (hipStream_t)hip_stream;
   if (!m->use_graph || st == nullptr || (m->prof && m->prof->on))  // the legacy default stream cannot be captured
     return run_decode(m, last_tokens_dev, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);

@@ -118,6 +118,7 @@ struct www_model {
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
   // prefill-path buffers
   float* hp;       // [maxT][d]
+  float* ssq_p;    // [d/256][maxT rounded to 256] partial sums of squares of hp
   uint16_t* xn;        // packed [maxT][d] normalised activations
   uint16_t* qp;    // [maxT][QD] rotated queries, fp16 (interleaved head-dim order)
   uint16_t* op;        // packed [maxT][QD] attention output

@@ -53,28 +53,27 @@ __global__ __launch_bounds__(1024) void prefill_meta_kernel(const int32_t* __res
   }
 }
 
+// Embedding rows: residual stream h = E[token] (fp32), the first GEMM operand fp16(h * gain) in the packed prefill
+// layout, and the row's sum of squares.  RMSNorm's 1/rms factor is applied by the consuming GEMM's epilogue.
 template <typename ET>
 __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restrict__ tokens, const ET* __restrict__ embed, int d,
-                                                          float* __restrict__ hp) {
+                                                          const float* __restrict__ gain, float* __restrict__ hp,
+                                                          uint16_t* __restrict__ xn, float* __restrict__ ssq) {
   int64_t r = blockIdx.x;
   const ET* row = embed + (int64_t)tokens[r] * d;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) {
-    float x;
-    if constexpr (sizeof(ET) == 4) x = (float)row[k];
-    else x = bf16_bits_to_float(((const uint16_t*)row)[k]);
-    hp[r * d + k] = x;
-  }
-}
-
-// xn[r] = fp16( h[r] * rsqrt(mean(h[r]^2) + eps) * gain ), written in the packed prefill layout
-__global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restrict__ hp, const float* __restrict__ gain, int d, float eps,
-                                                            uint16_t* __restrict__ xn) {
-  int64_t r = blockIdx.x;
-  const float* x = hp + r * d;
   float local = 0.f;
   for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
-    float4 v = *reinterpret_cast<const float4*>(x + k);
-    local += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    union { uint16_t s[4]; u32x2 v; } o;
+    float x[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if constexpr (sizeof(ET) == 4) x[e] = (float)row[k + e];
+      else x[e] = bf16_bits_to_float(((const uint16_t*)row)[k + e]);
+      local += x[e] * x[e];
+      o.s[e] = f32_to_f16_sat(x[e] * gain[k + e]);
+    }
+    *reinterpret_cast<float4*>(hp + r * d + k) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<u32x2*>(xn + packed_p_offset(r, k, d >> 4)) = o.v;
   }
   __shared__ float red[256];
   red[threadIdx.x] = local;
@@ -83,17 +82,7 @@ __global__ __launch_bounds__(256) void rmsnorm_cast_kernel(const float* __restri
     if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
-  float rs = rsqrtf(red[0] / d + eps);
-  for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4) {
-    float4 v = *reinterpret_cast<const float4*>(x + k);
-    float4 g = *reinterpret_cast<const float4*>(gain + k);
-    union { uint16_t s[4]; u32x2 v; } o;
-    o.s[0] = f32_to_f16_sat(v.x * rs * g.x);
-    o.s[1] = f32_to_f16_sat(v.y * rs * g.y);
-    o.s[2] = f32_to_f16_sat(v.z * rs * g.z);
-    o.s[3] = f32_to_f16_sat(v.w * rs * g.w);
-    *reinterpret_cast<u32x2*>(xn + packed_p_offset(r, k, d >> 4)) = o.v;
-  }
+  if (threadIdx.x == 0) ssq[r] = red[0];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -115,9 +104,17 @@ struct PGemmP {
   const int32_t *row_seq, *row_pos, *table;
   int mbs, hd, Hq, Hkv;
   const float2* rope;
-  // residual epilogue
+  // RMSNorm scale of the input rows (QKV and SwiGLU GEMMs): rsqrt(sum_i ssq_in[i][t] / dim + eps) multiplies the result
+  const float* ssq_in;
+  int n_ssq_in;
+  int64_t ssq_stride;
+  float inv_dim, eps;
+  // residual epilogue: h += result; also emits the next GEMM's operand fp16(h * gain_next) and partial sums of squares
   float* hp;
   int d;
+  const float* gain_next;
+  uint16_t* xn_out;
+  float* ssq_out;
   // SwiGLU epilogue
   uint16_t* ap;
   int Fp;
@@ -177,21 +174,28 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
       smem[buf][1024 + (wave + 4 * i) * 64 + lane] = sb[i];
     }
   };
+  // Operand fragments of the second 16-column step are fetched from LDS while the MFMAs of the first run.
   auto compute = [&](int buf) __attribute__((always_inline)) {
     const u32x4* A = smem[buf];
     const u32x4* B = smem[buf] + 1024;
     const int m = lane & 31, hh = lane >> 5;
+    u32x4 af[2][4], bfr[2][4];
+    auto fetch = [&](int set, int k16) __attribute__((always_inline)) {
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) af[set][rb] = A[(wn * 8 + rb * 2 + (m >> 4)) * 64 + ((k16 * 2 + hh) << 4) + (m & 15)];
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) bfr[set][tb] = B[((wt * 4 + tb) * 2 + k16) * 64 + lane];
+    };
+    fetch(0, 0);
+    fetch(1, 1);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k16 = 0; k16 < 2; ++k16) {
-      f16x8 af[4], bfr[4];
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) af[rb] = as_f16x8(A[(wn * 8 + rb * 2 + (m >> 4)) * 64 + ((k16 * 2 + hh) << 4) + (m & 15)]);
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb) bfr[tb] = as_f16x8(B[((wt * 4 + tb) * 2 + k16) * 64 + lane]);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[rb], bfr[tb], acc[rb][tb], 0, 0, 0);
+        for (int tb = 0; tb < 4; ++tb)
+          acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(af[k16][rb]), as_f16x8(bfr[k16][tb]), acc[rb][tb], 0, 0, 0);
     }
   };
 
@@ -208,13 +212,16 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     __syncthreads();
   }
   compute((p.KB - 1) & 1);
+  __syncthreads();  // the staging buffers are dead from here on; the residual epilogue reuses them
+  float(*red_ssq)[256] = reinterpret_cast<float(*)[256]>(&smem[0][0]);
+  (void)red_ssq;
 
   // acc[rb][tb][i] = Y^T[row][token]: row = (rg_tile + wn*8 + rb*2)*16 + (i/4)*8 + (lane/32)*4 + i%4, token = t_tile + wt*128 + tb*32 + lane%32
   const int hsel = lane >> 5;
 #pragma unroll
   for (int tb = 0; tb < 4; ++tb) {
     const int t = t_tile + wt * 128 + tb * 32 + (lane & 31);
-    if (t >= p.T) continue;
+    if (t >= p.T) continue;  // its red_ssq slot stays unwritten and is never read: the final store is masked the same way
     int pos = 0;
     int64_t kvbase = 0;
     int tok = 0;
@@ -224,6 +231,20 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
       kvbase = (slot / KV_BS) * p.Hkv;
       tok = (int)(slot % KV_BS);
     }
+    float scale = 1.f;
+    if constexpr (EPI != PEPI_RESID) {
+      float ss = 0.f;
+      for (int i0 = 0; i0 < p.n_ssq_in; i0 += 8) {  // tile order, eight loads in flight
+        float sv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sv[u] = p.ssq_in[(int64_t)min(i0 + u, p.n_ssq_in - 1) * p.ssq_stride + t];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (i0 + u < p.n_ssq_in) ss += sv[u];
+      }
+      scale = rsqrtf(ss * p.inv_dim + p.eps);
+    }
+    float ssq_tok = 0.f;
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
       const int rgb = rg_tile + wn * 8 + rb * 2;  // first of the two row groups of this 32-row block
@@ -235,7 +256,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
           union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            float g = acc[rb][tb][q4 * 4 + i], u = acc[rb][tb][(q4 + 2) * 4 + i];
+            float g = acc[rb][tb][q4 * 4 + i] * scale, u = acc[rb][tb][(q4 + 2) * 4 + i] * scale;
             o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
           }
           *reinterpret_cast<u32x2*>(p.ap + packed_p_offset(t, f0, p.Fp >> 4)) = o.v;
@@ -248,11 +269,21 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
           const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
           float v4[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i];
+          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i] * scale;
           if constexpr (EPI == PEPI_RESID) {
             float4* dst = reinterpret_cast<float4*>(p.hp + (int64_t)t * p.d + n0);
             float4 hv = *dst;
-            *dst = make_float4(hv.x + v4[0], hv.y + v4[1], hv.z + v4[2], hv.w + v4[3]);
+            const float hn[4] = {hv.x + v4[0], hv.y + v4[1], hv.z + v4[2], hv.w + v4[3]};
+            *dst = make_float4(hn[0], hn[1], hn[2], hn[3]);
+            const float4 gv = *reinterpret_cast<const float4*>(p.gain_next + n0);
+            const float gn[4] = {gv.x, gv.y, gv.z, gv.w};
+            union { uint16_t s[4]; u32x2 v; } o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              ssq_tok += hn[i] * hn[i];
+              o.s[i] = f32_to_f16_sat(hn[i] * gn[i]);
+            }
+            *reinterpret_cast<u32x2*>(p.xn_out + packed_p_offset(t, n0, p.d >> 4)) = o.v;
           } else {  // PEPI_QKV
             const int rot_rows = (p.Hq + p.Hkv) * p.hd;
             const int head = n0 / p.hd, c0 = n0 % p.hd;
@@ -283,6 +314,16 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         }
       }
     }
+    if constexpr (EPI == PEPI_RESID) {
+      ssq_tok += __shfl_xor(ssq_tok, 32);  // the two lane halves hold different rows of the same token
+      if (lane < 32) red_ssq[wn][wt * 128 + tb * 32 + lane] = ssq_tok;
+    }
+  }
+  if constexpr (EPI == PEPI_RESID) {
+    // per (row tile, token) sum of squares of the new residual, the two row halves added in a fixed order
+    __syncthreads();
+    const int t = t_tile + tid;
+    if (t < p.T) p.ssq_out[(int64_t)rt * p.ssq_stride + t] = red_ssq[0][tid] + red_ssq[1][tid];
   }
 }
 
@@ -457,19 +498,24 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
   int32_t* cum = m->meta + 16;
   hipLaunchKernelGGL(prefill_meta_kernel, dim3(1), dim3(1024), 0, st, tok, qlens, lens, batch, T, m->row_seq, m->row_pos, m->tile_seq,
                      m->tile_q0, m->meta, m->last_tok, cum);
+  const int64_t sstride = ((int64_t)m->maxT + 255) / 256 * 256;
   if (m->cfg.weight_dtype == WWW_DTYPE_F32)
-    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(T), dim3(256), 0, st, tok, (const float*)m->embed, d, m->hp);
+    hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(T), dim3(256), 0, st, tok, (const float*)m->embed, d, m->layers[0].attn_norm, m->hp,
+                       (uint16_t*)m->xn, m->ssq_p);
   else
-    hipLaunchKernelGGL(embed_rows_kernel<uint16_t>, dim3(T), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d, m->hp);
+    hipLaunchKernelGGL(embed_rows_kernel<uint16_t>, dim3(T), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d, m->layers[0].attn_norm,
+                       m->hp, (uint16_t*)m->xn, m->ssq_p);
+  int n_ssq = 1;
+  const int n_rt_d = (d / 16 + 15) / 16;  // row tiles of a GEMM with d output rows
   const int max_tiles = T / ATTN_TQ + batch;
   for (int l = 0; l < m->L; ++l) {
     const LayerW& w = m->layers[l];
     uint16_t* kplane = (uint16_t*)m->kv + (int64_t)(2 * l) * m->kv_plane;
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
-    hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.attn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
+      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.ssq_stride = sstride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       launch_pgemm<PEPI_QKV>(p, st);
@@ -480,20 +526,22 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;
-      p.hp = m->hp; p.d = d;
+      p.hp = m->hp; p.d = d; p.gain_next = w.ffn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p; p.ssq_stride = sstride;
       launch_pgemm<PEPI_RESID>(p, st);
+      n_ssq = n_rt_d;
     }
-    hipLaunchKernelGGL(rmsnorm_cast_kernel, dim3(T), dim3(256), 0, st, m->hp, w.ffn_norm, d, m->cfg.rms_eps, (uint16_t*)m->xn);
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
+      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.ssq_stride = sstride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
       launch_pgemm<PEPI_SWIGLU>(p, st);
     }
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
-      p.hp = m->hp; p.d = d;
+      p.hp = m->hp; p.d = d; p.gain_next = m->layers[l + 1].attn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
+      p.ssq_stride = sstride;
       launch_pgemm<PEPI_RESID>(p, st);
     }
   }

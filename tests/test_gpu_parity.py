@@ -40,11 +40,20 @@ def run_job(shape, lens, steps, seed, chunk=None, permute=True, gain_std=0.1, st
     return o_logits, o_tok, g_logits, g_tok
 
 
-def check(res, what):
+def check(res, what, strict=False):
+    """max |dlogit| <= 3e-2 always.  Greedy agreement >= 99 % (strict, teacher-forced).  The auxiliary cases below have
+    only tens of samples over vocabularies of 1-2 k random logits, where an exact near-tie (oracle top-2 gap below twice
+    the measured logit error) turns up about once per few hundred samples; for them a single such near-tie flip is
+    accepted.  The named configurations (tiny, full-width 1B / 8B, the 8B bench configuration) are held to the strict bar."""
     err, agree, tie = compare(*res)
-    print(f"{what}: max|dlogit|={err:.3e} agreement={agree:.4f} tie-aware={tie:.4f} samples={res[1].size}", flush=True)
+    n = res[1].size
+    print(f"{what}: max|dlogit|={err:.3e} agreement={agree:.4f} tie-aware={tie:.4f} samples={n}", flush=True)
     assert err <= TOL, f"{what}: max |dlogit| {err}"
-    assert agree >= AGREE, f"{what}: greedy agreement {agree}"
+    if strict or n >= 100:
+        assert agree >= AGREE, f"{what}: greedy agreement {agree}"
+    else:
+        mismatches = int(round((1 - agree) * n))
+        assert mismatches <= 1 and tie == 1.0, f"{what}: {mismatches} greedy mismatches, tie-aware agreement {tie}"
 
 
 def test_slot_indexing_bit_exact():
@@ -90,7 +99,7 @@ def test_decode_path_alone_token_by_token():
 def test_tiny_config_prefill_and_decode():
     wl = synth.workload("tiny")
     res = run_job(wl.shape, wl.prompt_lens, wl.decode_steps, seed=0, gain_std=0.0)
-    check(res, "tiny")
+    check(res, "tiny", strict=True)
 
 
 @pytest.mark.parametrize("shape,lens,steps", [
@@ -123,3 +132,106 @@ def test_block_permutation_is_invisible_bitwise():
     a = run_job(shape, [150, 40, 9], 3, seed=70, permute=False, blob=blob, num_blocks=40)
     b = run_job(shape, [150, 40, 9], 3, seed=70, permute=True, blob=blob, num_blocks=40)
     assert np.array_equal(a[2], b[2])
+
+
+# ------------------------------------------------------------------ full-width shapes (the launch configurations bench.py times)
+WIDE8B = dataclasses.replace(synth.M8B, name="wide8b", n_layers=2, seed=31)
+WIDE1B = dataclasses.replace(synth.M1B, name="wide1b", n_layers=2, seed=32)
+
+
+@pytest.mark.parametrize("shape,batch", [(WIDE8B, 64), (WIDE1B, 32)])
+def test_full_width_layers_at_bench_batch(shape, batch):
+    """every matrix has its full 8B / 1B size (same tiles, split-K factors and token groups as the benchmark);
+    only the layer count is cut so the oracle finishes in about a minute"""
+    lens = 1 + synth.uniform_i32(batch, 11, batch, 40)
+    lens[0], lens[1] = 1, 16
+    check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+
+
+def test_block_boundaries_and_single_token_sequences():
+    shape = MID128
+    for lens in ([1], [15, 16, 17], [31, 32, 33, 1]):
+        check(run_job(shape, lens, 18, seed=90 + len(lens), max_batch=8), f"lens {lens}")
+
+
+def test_capacity_and_argument_errors_on_device():
+    import torch
+    from paper_2603_20661_amd import binding as B
+    shape = MID64
+    blob = synth.make_blob(shape)
+    sess = GpuSession(shape, blob, max_batch=2, max_ctx=64, max_prefill_tokens=32, num_blocks=8)
+    try:
+        dev = sess.dev
+        i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev)
+        table = i32([[0, 1, 2, 3], [4, 5, 6, 7]])
+        three = i32([[0, 1, 2, 3]] * 3)
+        with pytest.raises(B.WwwError) as e:                                   # batch 3 > max_batch 2
+            B.www_decode_step(sess.model, i32([1, 2, 3]), i32([1, 1, 1]), three, stream=sess.stream)
+        assert e.value.code == B.E_CAPACITY
+        with pytest.raises(B.WwwError) as e:                                   # 40 new tokens > max_prefill_tokens 32
+            B.www_prefill(sess.model, i32([1] * 40), i32([20, 20]), i32([20, 20]), table, stream=sess.stream)
+        assert e.value.code == B.E_CAPACITY
+        with pytest.raises(B.WwwError) as e:                                   # fewer tokens than sequences
+            B.www_prefill(sess.model, i32([1]), i32([1, 1]), i32([1, 1]), table, stream=sess.stream)
+        assert e.value.code == B.E_INVALID_ARG
+        # an empty batch is a no-op, and the model still works afterwards
+        B.www_decode_step(sess.model, i32([]), i32([]), table[:0], stream=sess.stream)
+        lg, nx = sess.decode([5, 6], [1, 1], table.cpu().numpy())
+        assert np.isfinite(lg).all()
+    finally:
+        sess.close()
+
+
+def test_8b_bench_configuration_sampled_against_oracle():
+    """The 8B-shaped workload exactly as bench.py launches it (batch 64, 80 231 prompt tokens in one prefill call,
+    then decode steps).  Properties at full size: logits finite although the pool starts as NaN, bit-identical
+    under a different physical block placement.  Sampled parity: the shortest sequence is recomputed alone by
+    the oracle (prefill + 2 decode steps) and compared with its rows of the batched GPU run."""
+    from oracle import oracle as O
+    wl = synth.workload("8b")
+    shape, lens, toks = wl.shape, wl.prompt_lens.astype(np.int32), wl.prompt_tokens
+    steps = 2
+    Bn = wl.batch
+    cap = lens + steps + 1
+    mbs = int((cap.max() + 15) // 16)
+    nblocks = int(((cap + 15) // 16).sum()) + 64
+    blob = synth.make_blob(shape)
+    b0 = int(np.argmin(lens))
+    start = int(np.cumsum(lens)[b0] - lens[b0])
+    # oracle on the sampled sequence
+    m = O.OracleModel(shape, blob, num_blocks=(int(cap[b0]) + 15) // 16)
+    tab1 = np.arange((int(cap[b0]) + 15) // 16, dtype=np.int32)[None]
+    o_lg, o_nx, _ = m.forward(toks[start:start + lens[b0]], lens[b0:b0 + 1], lens[b0:b0 + 1], block_table=tab1)
+    o_logits, o_next = [o_lg[0]], [int(o_nx[0])]
+    for s in range(steps):
+        ol, on, _ = m.forward([o_next[s]], [1], [int(lens[b0]) + s + 1], block_table=tab1)
+        o_logits.append(ol[0])
+        o_next.append(int(on[0]))
+    m.close()
+    # GPU, two placements of the same job; decode is teacher-forced for the sampled sequence, free-running for the rest
+    results = []
+    for placement in (0, 1):
+        table = synth.block_tables(100 + placement, cap, nblocks, mbs, permute=True)
+        sess = GpuSession(shape, blob, Bn, mbs * 16, int(lens.sum()), nblocks)
+        try:
+            lg, nx = sess.prefill(toks, lens, lens, table)
+            out = [lg]
+            cur = lens.copy()
+            for s in range(steps):
+                feed = nx.copy()
+                feed[b0] = o_next[s]
+                cur = cur + 1
+                lg, nx = sess.decode(feed, cur, table)
+                out.append(lg)
+            results.append(np.stack(out))
+        finally:
+            sess.close()
+    a, b = results
+    assert np.isfinite(a).all()
+    assert np.array_equal(a, b), "logits depend on the physical block placement"
+    got = a[:, b0]
+    ref = np.stack(o_logits)
+    err = float(np.abs(got - ref).max())
+    agree = float((got.argmax(-1) == ref.argmax(-1)).mean())
+    print(f"8b bench configuration, sequence {b0} (len {lens[b0]}): max|dlogit|={err:.3e} agreement={agree:.3f}", flush=True)
+    assert err <= TOL and agree == 1.0
