@@ -126,7 +126,8 @@ const char* www_last_error(void);
 int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream);
 
 /* Test hook: copies an internal fp32 buffer of the last call to host memory after synchronising the
- * stream.  which: 0 = residual stream of the decode path [batch][d_model].
+ * stream.  which: 0 = residual stream of the decode path [batch][d_model]; 1 = the decode path's query buffer and
+ * 2 = its packed attention output, both as raw 32-bit words.
  * Errors: INVALID_ARG, HIP. */
 int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream);
 

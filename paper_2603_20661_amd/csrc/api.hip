@@ -152,7 +152,7 @@ static void make_plan(const www_config* c, Plan& p) {
       }
   }
   p.partial = take(part ? part : 256);
-  p.attn_kps = 256;
+  p.attn_kps = 512;  // keys per decode-attention split (a split spans at most 64 blocks, i.e. 1024 keys)
   p.attn_splits = (s.max_pos + p.attn_kps - 1) / p.attn_kps;
   p.attn_part = take((uint64_t)s.maxB * s.Hkv * p.attn_splits * s.G * (s.hd + 4) * 4);
   p.logits = take((uint64_t)s.maxB * s.V * 4);
@@ -282,7 +282,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->rope = (const float2*)(ws + p.rope);
   m->kv = (uint16_t*)kv_pool_dev;
   m->kv_plane = (int64_t)cfg->num_kv_blocks * s.Hkv * KV_BS * s.hd;
-  m->h = (float*)(ws + p.h); m->ssq = (float*)(ws + p.ssq); m->q = (float*)(ws + p.q);
+  m->h = (float*)(ws + p.h); m->ssq = (float*)(ws + p.ssq); m->q_hi = (uint16_t*)(ws + p.q); m->q_lo = m->q_hi + (size_t)s.MTmax * 16 * s.QD;
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
   m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
   m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
@@ -377,6 +377,8 @@ WWW_EXPORT int www_debug_read(www_model* m, int32_t which, float* dst_host, uint
   const float* src = nullptr;
   uint64_t cap = 0;
   if (which == 0) { src = m->h; cap = (uint64_t)m->MTmax * 16 * m->d; }
+  else if (which == 1) { src = (const float*)m->q_hi; cap = (uint64_t)m->MTmax * 16 * m->QD; }  // raw fp16 hi then lo planes
+  else if (which == 2) { src = (const float*)m->xo; cap = (uint64_t)m->MTmax * 16 * m->QD; }    // raw packed attention output
   else { set_error("unknown buffer %d", which); return WWW_E_INVALID_ARG; }
   if (n_floats > cap) { set_error("buffer holds %llu floats", (unsigned long long)cap); return WWW_E_INVALID_ARG; }
   HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));

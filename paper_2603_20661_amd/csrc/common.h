@@ -107,7 +107,7 @@ struct www_model {
   // decode-path buffers
   float* h;        // [maxB][d] residual stream
   float* ssq;      // [SSQ_TILES][maxB] partial sums of squares of h
-  float* q;        // [maxB][QD]
+  uint16_t *q_hi, *q_lo;  // [maxB][QD] rotated, pre-scaled queries as fp16 hi + lo
   uint16_t* xq;        // packed activations feeding the QKV / gate-up / lm_head GEMMs (K = d)
   uint16_t* xo;        // packed attention output feeding the O projection (K = QD)
   uint16_t* xa;        // packed SwiGLU output feeding the down projection (K = Fp)

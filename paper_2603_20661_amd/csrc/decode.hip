@@ -102,7 +102,8 @@ struct GemmP {
   int n_ssq_in, ssq_stride;
   float inv_dim, eps;
   // QKV epilogue
-  float* q;
+  uint16_t *q_hi, *q_lo;
+  float qscale;
   uint16_t *kplane, *vplane;  // this layer's K and V planes of the pool
   const int32_t *seq_lens, *table;
   int mbs, hd, Hq, Hkv;
@@ -387,7 +388,12 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
             }
           }
           if (head < p.Hq) {
-            *reinterpret_cast<float4*>(p.q + (int64_t)t * (p.Hq * p.hd) + n0) = make_float4(v[0], v[1], v[2], v[3]);
+            // queries leave as fp16 hi + lo, already multiplied by log2(e)/sqrt(hd), in the order the attention kernel loads them
+            union { uint16_t s[4]; u32x2 v; } qh, ql;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) split_f16(v[i] * p.qscale, qh.s[i], ql.s[i]);
+            *reinterpret_cast<u32x2*>(p.q_hi + (int64_t)t * (p.Hq * p.hd) + n0) = qh.v;
+            *reinterpret_cast<u32x2*>(p.q_lo + (int64_t)t * (p.Hq * p.hd) + n0) = ql.v;
           } else {
             const int64_t slot = slot_pre[tb];
             const int64_t blk = slot / KV_BS;
@@ -434,41 +440,43 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 // Partial results (m, l, unnormalised o) of all splits of a (sequence, kv head) are merged by the
 // wavefront that finishes last, which also writes the packed hi/lo operand of the O projection.
 template <int HD, int G>
-__global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict__ q, const uint16_t* __restrict__ kplane,
+__global__ __launch_bounds__(64) void decode_attn_kernel(const uint16_t* __restrict__ q_hi, const uint16_t* __restrict__ q_lo,
+                                                          const uint16_t* __restrict__ kplane,
                                                           const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
                                                           const int32_t* __restrict__ table, int mbs, int Hq, int Hkv, int kps,
-                                                          float qscale, float* __restrict__ part, int* __restrict__ counters,
-                                                          uint16_t* __restrict__ xo, int MT) {
+                                                          float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
   constexpr int NKF = HD / 32;  // K fragments per block
   constexpr int NVF = HD / 16;  // V fragments per block
   constexpr int PSTRIDE = HD + 4;  // floats per (split, head) partial record: o[HD], m, l, pad
   const int split = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x;
   const int n = lane & 15, g = lane >> 4;
-  const int ctx = seq_lens[b];
   const int k0 = split * kps;
+  const int32_t* trow = table + (int64_t)b * mbs;
+  // block ids of this split, one per lane (a split spans at most 64 blocks); independent of the sequence length so that
+  // this load, the length and the queries are all in flight together.  Entries past the sequence's last block are unused.
+  const int blk0 = k0 / KV_BS;
+  const int my_blk = trow[min(blk0 + lane, mbs - 1)];
+  const int ctx = __builtin_amdgcn_readfirstlane(seq_lens[b]);  // wave-uniform: keeps loop bounds and lane selects scalar
+  // Q^T operand: lane (head n, group g) holds dims f*32 + g*8 .. +7 of head n, as fp16 hi + lo (pre-scaled by the producer)
+  f16x8 qhi[NKF], qlo[NKF];
+  {
+    const int64_t qoff = ((int64_t)b * Hq + j * G + min(n, G - 1)) * HD + g * 8;
+#pragma unroll
+    for (int f = 0; f < NKF; ++f) {
+      u32x4 h = *reinterpret_cast<const u32x4*>(q_hi + qoff + f * 32);
+      u32x4 l = *reinterpret_cast<const u32x4*>(q_lo + qoff + f * 32);
+      if (n >= G) { h = u32x4{0, 0, 0, 0}; l = u32x4{0, 0, 0, 0}; }
+      qhi[f] = as_f16x8(h);
+      qlo[f] = as_f16x8(l);
+    }
+  }
   if (k0 >= ctx) return;
   const int nsplit_act = (ctx + kps - 1) / kps;
   const int nsplit_max = gridDim.x;
   const int kend = min(ctx, k0 + kps);
   const int npairs = (kend - k0 + 31) / 32;
-  const int32_t* trow = table + (int64_t)b * mbs;
-  const int last_blk = (ctx - 1) / KV_BS;
-
-  // Q^T operand: lane (head n, group g) holds dims f*32 + g*8 .. +7 of head n, as hi + lo
-  f16x8 qhi[NKF], qlo[NKF];
-#pragma unroll
-  for (int f = 0; f < NKF; ++f) {
-    union { uint16_t s[8]; f16x8 v; } hi, lo;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x = 0.f;
-      if (n < G) x = q[((int64_t)b * Hq + j * G + n) * HD + f * 32 + g * 8 + e] * qscale;
-      split_f16(x, hi.s[e], lo.s[e]);
-    }
-    qhi[f] = hi.v;
-    qlo[f] = lo.v;
-  }
+  const int last_blk_local = (kend - 1) / KV_BS - blk0;  // index, within this split, of its last valid block
 
   f32x4 oacc[NVF];
 #pragma unroll
@@ -476,17 +484,14 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
   float m_run = NEG_INF, l_run = 0.f;
 
   const int64_t blk_elems = (int64_t)KV_BS * HD;
-  // physical ids of this split's blocks, one per lane, fetched once (a split spans at most 64 blocks)
-  const int blk0 = k0 / KV_BS;
-  const int my_blk = trow[min(blk0 + lane, last_blk)];
 
   struct KV {
     u32x4 k0[NKF], k1[NKF];
     u32x2 v0[NVF], v1[NVF];
   };
   auto load_pair = [&](KV& r, int pr) __attribute__((always_inline)) {
-    const int id0 = __builtin_amdgcn_readlane(my_blk, min(2 * pr, 63));
-    const int id1 = __builtin_amdgcn_readlane(my_blk, min(2 * pr + 1, 63));  // past the sequence end this repeats the last block (masked)
+    const int id0 = __shfl(my_blk, min(2 * pr, last_blk_local));
+    const int id1 = __shfl(my_blk, min(2 * pr + 1, last_blk_local));  // past the end: the last block again (masked)
     const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
     const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
 #pragma unroll
@@ -533,22 +538,16 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    // values of masked keys must not reach the MFMA (0 * NaN): clear them in the tail pair
-    if (base + 32 > kend) {
-      const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
-      const uint32_t a01 = (ka + 0 < kend ? 0xFFFFu : 0u) | (ka + 1 < kend ? 0xFFFF0000u : 0u);
-      const uint32_t a23 = (ka + 2 < kend ? 0xFFFFu : 0u) | (ka + 3 < kend ? 0xFFFF0000u : 0u);
-      const uint32_t b01 = (kb2 + 0 < kend ? 0xFFFFu : 0u) | (kb2 + 1 < kend ? 0xFFFF0000u : 0u);
-      const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
-#pragma unroll
-      for (int f = 0; f < NVF; ++f) {
-        r.v0[f].x &= a01; r.v0[f].y &= a23;
-        r.v1[f].x &= b01; r.v1[f].y &= b23;
-      }
-    }
+    // values of masked keys must not reach the MFMA (0 * NaN): clear them.  Done for every pair, without a branch:
+    // the masks are all-ones except in a split's last pair.
+    const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
+    const uint32_t a01 = (ka + 0 < kend ? 0xFFFFu : 0u) | (ka + 1 < kend ? 0xFFFF0000u : 0u);
+    const uint32_t a23 = (ka + 2 < kend ? 0xFFFFu : 0u) | (ka + 3 < kend ? 0xFFFF0000u : 0u);
+    const uint32_t b01 = (kb2 + 0 < kend ? 0xFFFFu : 0u) | (kb2 + 1 < kend ? 0xFFFF0000u : 0u);
+    const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      u32x4 a = {r.v0[f].x, r.v0[f].y, r.v1[f].x, r.v1[f].y};
+      const u32x4 a = {r.v0[f].x & a01, r.v0[f].y & a23, r.v1[f].x & b01, r.v1[f].y & b23};
       oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
       oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
     }
@@ -596,27 +595,32 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
     return;
   }
 
-  // park this split's record: [b][j][split][head n][o(HD), m, l]
+  // park this split's record [b][j][split][head n][o(HD), m, l]; a separate small kernel merges the records of
+  // split sequences (a kernel boundary is a far cheaper hand-over here than in-kernel device-scope signalling)
   float* rec = part + ((((int64_t)b * Hkv + j) * nsplit_max + split) * G) * PSTRIDE;
-  const __amdgpu_buffer_rsrc_t part_rs = shared_rsrc(part);
   if (n < G) {
 #pragma unroll
     for (int f = 0; f < NVF; ++f)
-      store_shared_f32x4(part_rs, (uint32_t)((rec - part) + n * PSTRIDE + f * 16 + g * 4) * 4u, oacc[f]);
+      *reinterpret_cast<float4*>(rec + n * PSTRIDE + f * 16 + g * 4) = make_float4(oacc[f][0], oacc[f][1], oacc[f][2], oacc[f][3]);
     if (g == 0) {
-      store_shared_f32(rec + n * PSTRIDE + HD, m_run);
-      store_shared_f32(rec + n * PSTRIDE + HD + 1, l_run);
+      rec[n * PSTRIDE + HD] = m_run;
+      rec[n * PSTRIDE + HD + 1] = l_run;
     }
   }
-  wait_own_memory_ops();
-  int old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(&counters[b * Hkv + j], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  old = __shfl(old, 0);
-  if (old != nsplit_act - 1) return;
-  if (lane == 0) __hip_atomic_store(&counters[b * Hkv + j], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-  // Merge all splits in split order.  Lane owns head-dim elements lane + 64*i of every head; records are read
-  // four splits at a time so the merge is not one memory round trip per split.
+// Merges the split records of one (sequence, kv head) in split order and writes the packed hi/lo operand of the O
+// projection.  One wavefront per (kv head, sequence); sequences that fitted into one split were finished by the
+// attention kernel itself.
+template <int HD, int G>
+__global__ __launch_bounds__(64) void decode_attn_merge_kernel(const int32_t* __restrict__ seq_lens, int Hkv, int kps, int nsplit_max,
+                                                                const float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
+  constexpr int PSTRIDE = HD + 4;
+  const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+  const int nsplit_act = (seq_lens[b] + kps - 1) / kps;
+  if (nsplit_act <= 1) return;
+  // Lane owns head-dim elements lane + 64*i of every head; records are read four splits at a time so the merge is
+  // not one memory round trip per split.
   const float* recs = part + (((int64_t)b * Hkv + j) * nsplit_max) * G * PSTRIDE;
   constexpr int NE = HD / 64;
   float Mh[G], Lh[G], oh[G][NE];
@@ -635,10 +639,10 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const float* __restrict
 #pragma unroll
       for (int hh = 0; hh < G; ++hh) {
         const float* r = recs + ((int64_t)sidx * G + hh) * PSTRIDE;
-        mv[u][hh] = load_shared_f32(r + HD);
-        lv[u][hh] = load_shared_f32(r + HD + 1);
+        mv[u][hh] = r[HD];
+        lv[u][hh] = r[HD + 1];
 #pragma unroll
-        for (int i = 0; i < NE; ++i) ov[u][hh][i] = load_shared_f32(r + lane + 64 * i);
+        for (int i = 0; i < NE; ++i) ov[u][hh][i] = r[lane + 64 * i];
       }
     }
 #pragma unroll
@@ -772,7 +776,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       p.W = (const u32x4*)w.wqkv; p.Wlo = (const u32x4*)w.wqkv_lo; p.NRG = m->QKVN / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
-      p.q = m->q; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
+      p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
       p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       prof_mark(m, PK_QKV, st);
       launch_gemm<EPI_QKV>(m, p, MT, st);
@@ -781,13 +785,17 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       dim3 grid(m->attn_splits, m->Hkv, batch);
       prof_mark(m, PK_ATTN, st);
 #define ATTN(HD_, G_)                                                                                                              \
-  hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q, kplane, vplane, lens, table,                       \
-                     (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, qscale, m->attn_part, m->counters + 65536,          \
-                     (uint16_t*)m->xo, MT)
+  {                                                                                                                                \
+    hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q_hi, m->q_lo, kplane, vplane, lens, table,                     \
+                       (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, m->attn_part, (uint16_t*)m->xo, MT);     \
+    if (m->attn_splits > 1)                                                                                                        \
+      hipLaunchKernelGGL((decode_attn_merge_kernel<HD_, G_>), dim3(m->Hkv, batch), dim3(64), 0, st, lens, m->Hkv, m->attn_kps,      \
+                         m->attn_splits, m->attn_part, (uint16_t*)m->xo, MT);                                                      \
+  }
       if (m->hd == 128) {
-        if (m->G == 1) ATTN(128, 1); else if (m->G == 2) ATTN(128, 2); else if (m->G == 4) ATTN(128, 4); else ATTN(128, 8);
+        if (m->G == 1) ATTN(128, 1) else if (m->G == 2) ATTN(128, 2) else if (m->G == 4) ATTN(128, 4) else ATTN(128, 8)
       } else {
-        if (m->G == 1) ATTN(64, 1); else if (m->G == 2) ATTN(64, 2); else if (m->G == 4) ATTN(64, 4); else ATTN(64, 8);
+        if (m->G == 1) ATTN(64, 1) else if (m->G == 2) ATTN(64, 2) else if (m->G == 4) ATTN(64, 4) else ATTN(64, 8)
       }
 #undef ATTN
     }

@@ -125,6 +125,17 @@ def test_long_context_many_splits():
     check(run_job(MID128, [1100, 520], 2, seed=60), "long context")
 
 
+@pytest.mark.parametrize("hd", [64, 128])
+@pytest.mark.parametrize("group", [1, 2, 4, 8])
+def test_every_head_dim_and_group_size(hd, group):
+    """each (head_dim, query heads per kv head) pair is its own instantiation of the attention kernels: run every one over
+    contexts of one key pair, several pairs, and several splits plus the merge"""
+    n_kv = 2 if group <= 4 else 1
+    shape = synth.ModelShape(f"hd{hd}g{group}", 1, 256, n_kv * group, n_kv, hd, 352, 512, 1e-5, 1e4, synth.WDTYPE_BF16,
+                             seed=100 + hd + group)
+    check(run_job(shape, [1045, 3, 31, 530, 64], 3, seed=80 + group), shape.name)
+
+
 def test_block_permutation_is_invisible_bitwise():
     """GPU vs GPU: identity and permuted block tables give bit-identical logits"""
     shape = MID128
