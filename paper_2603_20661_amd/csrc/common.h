@@ -74,8 +74,11 @@ __device__ __forceinline__ int k_cache_offset(int tok, int c) { return ((c >> 5)
 __device__ __forceinline__ int v_cache_offset(int tok, int c) { return ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3); }
 
 // physical token slot of logical position pos of a sequence with block-table row `row`
+// (split in two so that a kernel can issue the table load early and finish the arithmetic where the slot is used)
+__device__ __forceinline__ int32_t kv_block_id(const int32_t* __restrict__ row, int pos) { return row[pos / KV_BS]; }
+__device__ __forceinline__ int64_t kv_slot_in_block(int32_t block_id, int pos) { return (int64_t)block_id * KV_BS + (pos % KV_BS); }
 __device__ __forceinline__ int64_t kv_slot(const int32_t* __restrict__ row, int pos) {
-  return (int64_t)row[pos / KV_BS] * KV_BS + (pos % KV_BS);
+  return kv_slot_in_block(kv_block_id(row, pos), pos);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -106,7 +109,7 @@ struct www_model {
   int64_t kv_plane;  // elements per (layer, K|V) plane = num_blocks * Hkv * 16 * hd
   // decode-path buffers
   float* h;        // [maxB][d] residual stream
-  float* ssq;      // [SSQ_TILES][maxB] partial sums of squares of h
+  float* ssq;      // [maxB][SSQ_TILES] partial sums of squares of h, one per row tile of the producing GEMM
   uint16_t *q_hi, *q_lo;  // [maxB][QD] rotated, pre-scaled queries as fp16 hi + lo
   uint16_t* xq;        // packed activations feeding the QKV / gate-up / lm_head GEMMs (K = d)
   uint16_t* xo;        // packed attention output feeding the O projection (K = QD)

@@ -10,21 +10,6 @@
 
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
-// sum of the per-tile partial sums of squares of token t, added in tile order (reproducible); loads go out eight at a
-// time so the chain costs a few memory round trips instead of one per tile
-__device__ __forceinline__ float ssq_total(const float* __restrict__ ssq, int n_tiles, int stride, int t) {
-  float s = 0.f;
-  for (int i0 = 0; i0 < n_tiles; i0 += 8) {
-    float v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = ssq[min(i0 + u, n_tiles - 1) * stride + t];
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (i0 + u < n_tiles) s += v[u];
-  }
-  return s;
-}
-
 // Cross-workgroup hand-over of partial results inside one kernel.  Partial tiles are written and read with
 // device-scope relaxed atomic accesses, which go through to memory shared by all XCDs instead of living in one
 // XCD's write-back L2; the producer waits for its stores to complete, the workgroup syncs, and one thread bumps a
@@ -82,7 +67,7 @@ __global__ __launch_bounds__(256) void embed_pack_kernel(const int32_t* __restri
     if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
-  if (threadIdx.x == 0) ssq[t] = red[0];
+  if (threadIdx.x == 0) ssq[(int64_t)t * SSQ_TILES] = red[0];  // row t of the [token][row tile] table; one entry in use
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -98,8 +83,8 @@ struct GemmP {
   int kb_per_split, ksplit;
   float* partial;    // [ksplit][MT*16][NRG*16]
   int* counters;     // [gridDim.z][gridDim.x]
-  const float* ssq_in;  // row scale = rsqrt(sum(ssq_in)/dim + eps), or null for no scale
-  int n_ssq_in, ssq_stride;
+  const float* ssq_in;  // [token][SSQ_TILES]; row scale = rsqrt(sum of the first n_ssq_in entries / dim + eps); null: no scale
+  int n_ssq_in;
   float inv_dim, eps;
   // QKV epilogue
   uint16_t *q_hi, *q_lo;
@@ -150,26 +135,46 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 #pragma unroll
     for (int tb = 0; tb < MTK; ++tb) acc[r][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Inputs of the epilogue that hang off dependent loads (RMSNorm scale; position and KV slot of each token) are
-  // fetched now, so their latency hides behind the main loop.
-  float scale_pre[MTK];
+  // Inputs of the epilogue that hang off dependent loads (RMSNorm scale; position and KV block of each token) are
+  // requested at kernel entry together with the first weights and activations, and only touched once that first chunk
+  // has arrived, so they never put a memory round trip in front of the streaming loop.
+  // Sum of squares of token t: lane group g = lane/16 reads entries 16g .. 16g+15 of the token's row (four 16-byte
+  // loads, always in bounds; entries past n_ssq_in are masked), adds them in index order, and the four groups are
+  // combined by two cross-lane exchanges: a fixed order, so the scale is the same in every workgroup.
+  f32x4 ssq_raw[MTK][4];
   int pos_pre[MTK];
-  int64_t slot_pre[MTK];
+  int tok_c[MTK];
 #pragma unroll
   for (int tb = 0; tb < MTK; ++tb) {
-    const int t = (tb0 + tb) * 16 + (lane & 15);
-    const bool tok_ok = t < p.M;
-    scale_pre[tb] = 1.f;
+    tok_c[tb] = min((tb0 + tb) * 16 + (lane & 15), p.M - 1);
     pos_pre[tb] = 0;
-    slot_pre[tb] = 0;
-    if (p.ssq_in && tok_ok) scale_pre[tb] = rsqrtf(ssq_total(p.ssq_in, p.n_ssq_in, p.ssq_stride, t) * p.inv_dim + p.eps);
-    if constexpr (EPI == EPI_QKV) {
-      if (tok_ok) {
-        pos_pre[tb] = p.seq_lens[t] - 1;
-        slot_pre[tb] = kv_slot(p.table + (int64_t)t * p.mbs, pos_pre[tb]);
-      }
+    if (p.ssq_in) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        ssq_raw[tb][c] = *reinterpret_cast<const f32x4*>(p.ssq_in + (int64_t)tok_c[tb] * SSQ_TILES + (lane >> 4) * 16 + c * 4);
     }
+    if constexpr (EPI == EPI_QKV) pos_pre[tb] = p.seq_lens[tok_c[tb]] - 1;
   }
+  float scale_pre[MTK];
+  int blk_pre[MTK];
+  auto finish_prefetch = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int tb = 0; tb < MTK; ++tb) {
+      scale_pre[tb] = 1.f;
+      blk_pre[tb] = 0;
+      if (p.ssq_in) {
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s += ((lane >> 4) * 16 + c * 4 + e < p.n_ssq_in) ? ssq_raw[tb][c][e] : 0.f;
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        scale_pre[tb] = rsqrtf(s * p.inv_dim + p.eps);
+      }
+      if constexpr (EPI == EPI_QKV) blk_pre[tb] = kv_block_id(p.table + (int64_t)tok_c[tb] * p.mbs, pos_pre[tb]);
+    }
+  };
 
   u32x4 wA[KC][R][WP], wB[KC][R][WP], stg[NSTG];
 
@@ -239,7 +244,9 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     const int last_valid = (kb_end - kb_begin) - (nchunks - 1) * KC;  // k blocks in the final chunk
     load_stage(0);
     load_w(wA, 0);
+    __builtin_amdgcn_sched_barrier(0);
     store_stage(0);
+    finish_prefetch();
     __syncthreads();
     int c = 0;
     for (; c + 2 < nchunks; c += 2) {
@@ -271,12 +278,33 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
       compute(wA, 0, last_valid);
     }
     __syncthreads();
+  } else {
+    finish_prefetch();
   }
 
   // accumulator layout: acc[r][tb][i] = Y^T[row][token], row = (rg0+r)*16 + (lane/16)*4 + i, token = (tb0+tb)*16 + lane%16
   const int rsub = (lane >> 4) * 4;
   const int tsub = lane & 15;
 
+  // Operands of the epilogue that live in memory (residual stream and next norm's gain; rotary factors) are requested
+  // before the split-K partial tiles, so the last workgroup pays one memory round trip for everything it needs.
+  // Addresses are clamped into range; values of invalid rows / tokens are never used.
+  f32x4 hv_pre[R][MTK], gv_pre[R], cs_pre[R][MTK];
+  auto request_epilogue_inputs = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int n0 = rgc[r] * 16 + rsub;
+      if constexpr (EPI == EPI_RESID) gv_pre[r] = *reinterpret_cast<const f32x4*>(p.gain_next + n0);
+#pragma unroll
+      for (int tb = 0; tb < MTK; ++tb) {
+        if constexpr (EPI == EPI_RESID) hv_pre[r][tb] = *reinterpret_cast<const f32x4*>(p.h + (int64_t)tok_c[tb] * p.d + n0);
+        if constexpr (EPI == EPI_QKV)
+          cs_pre[r][tb] = *reinterpret_cast<const f32x4*>(p.rope + (int64_t)pos_pre[tb] * (p.hd / 2) + ((n0 % p.hd) >> 1));
+      }
+    }
+  };
+
+  if (p.ksplit <= 1) request_epilogue_inputs();
   if (p.ksplit > 1) {
     // split-K: park the partial tile, and let the workgroup that arrives last add all partial tiles in split order
     // parked as a register image: unit ((((split, zb, tile), wave), r), tb), lane -> one 16-byte store per lane,
@@ -298,6 +326,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     __syncthreads();
     if (!*s_last) return;
     if (tid == 0) __hip_atomic_store(&p.counters[zb * gridDim.x + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    request_epilogue_inputs();
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -360,10 +389,9 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
         if constexpr (EPI == EPI_LOGITS) {
           *reinterpret_cast<float4*>(p.logits + (int64_t)t * p.V + n0) = make_float4(v[0], v[1], v[2], v[3]);
         } else if constexpr (EPI == EPI_RESID) {
-          float4 hv = *reinterpret_cast<const float4*>(p.h + (int64_t)t * p.d + n0);
-          float4 gv = *reinterpret_cast<const float4*>(p.gain_next + n0);
-          float hn[4] = {hv.x + v[0], hv.y + v[1], hv.z + v[2], hv.w + v[3]};
-          float gn[4] = {gv.x, gv.y, gv.z, gv.w};
+          const f32x4 hv = hv_pre[r][tb], gv = gv_pre[r];
+          float hn[4] = {hv[0] + v[0], hv[1] + v[1], hv[2] + v[2], hv[3] + v[3]};
+          float gn[4] = {gv[0], gv[1], gv[2], gv[3]};
           *reinterpret_cast<float4*>(p.h + (int64_t)t * p.d + n0) = make_float4(hn[0], hn[1], hn[2], hn[3]);
           union { uint16_t s[4]; u32x2 v; } hi, lo;
 #pragma unroll
@@ -374,17 +402,16 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
           *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 0)) = hi.v;
           *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 1)) = lo.v;
         } else {  // EPI_QKV
-          const int pos = pos_pre[tb];
           const int rot_rows = (p.Hq + p.Hkv) * p.hd;
           const int head = n0 / p.hd, c0 = n0 % p.hd;
           if (n0 < rot_rows) {
             // rows arrive with the rotary pair (i, i + hd/2) at neighbouring positions (2i, 2i+1)
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
-              float2 cs = p.rope[(int64_t)pos * (p.hd / 2) + (c0 >> 1) + pr];
+              const float cs_x = cs_pre[r][tb][2 * pr], cs_y = cs_pre[r][tb][2 * pr + 1];
               float a = v[2 * pr], b = v[2 * pr + 1];
-              v[2 * pr] = a * cs.x - b * cs.y;
-              v[2 * pr + 1] = b * cs.x + a * cs.y;
+              v[2 * pr] = a * cs_x - b * cs_y;
+              v[2 * pr + 1] = b * cs_x + a * cs_y;
             }
           }
           if (head < p.Hq) {
@@ -395,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
             *reinterpret_cast<u32x2*>(p.q_hi + (int64_t)t * (p.Hq * p.hd) + n0) = qh.v;
             *reinterpret_cast<u32x2*>(p.q_lo + (int64_t)t * (p.Hq * p.hd) + n0) = ql.v;
           } else {
-            const int64_t slot = slot_pre[tb];
+            const int64_t slot = kv_slot_in_block(blk_pre[tb], pos_pre[tb]);
             const int64_t blk = slot / KV_BS;
             const int tok = (int)(slot % KV_BS);
             if (head < p.Hq + p.Hkv) {
@@ -428,7 +455,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     __syncthreads();
     if (tid < MTK * 16) {
       int t = tb0 * 16 + tid;
-      if (t < p.M) p.ssq_out[tile * p.ssq_stride + t] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+      if (t < p.M) p.ssq_out[(int64_t)t * SSQ_TILES + tile] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
     }
   }
 }
@@ -702,13 +729,21 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
 // ------------------------------------------------------------------------------------------------
 // Host side
 
-// Workgroups a skinny GEMM should spread over (split-K is used when the row tiles alone are fewer).  Tunable
-// through the environment variable WWW_GEMM_WG_TARGET, read once.
+// Workgroups a skinny GEMM should spread over (split-K is used when the row tiles alone are fewer): one per compute
+// unit, so that no compute unit carries two of a kernel's workgroups while others carry one.  Tunable through the
+// environment variable WWW_GEMM_WG_TARGET, read once.
 static int wg_target() {
   static int v = 0;
   if (!v) {
     const char* e = getenv("WWW_GEMM_WG_TARGET");
-    v = e ? atoi(e) : 320;
+    if (e) {
+      v = atoi(e);
+    } else {
+      int dev = 0, cus = 0;
+      if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) v = cus;
+      else (void)hipGetLastError();
+      if (v < 1) v = 256;
+    }
     if (v < 1) v = 1;
   }
   return v;
@@ -765,7 +800,6 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     hipLaunchKernelGGL(embed_pack_kernel<uint16_t>, dim3(batch), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d,
                        m->layers[0].attn_norm, m->h, m->ssq, (uint16_t*)m->xq, MT);
   int n_ssq = 1;
-  const int stride = m->maxB;
   const float qscale = 1.4426950408889634f / sqrtf((float)m->hd);
   for (int l = 0; l < m->L; ++l) {
     const LayerW& w = m->layers[l];
@@ -775,7 +809,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       GemmP p = {};
       p.W = (const u32x4*)w.wqkv; p.Wlo = (const u32x4*)w.wqkv_lo; p.NRG = m->QKVN / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
-      p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
+      p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
       p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       prof_mark(m, PK_QKV, st);
@@ -803,7 +837,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       GemmP p = {};
       p.W = (const u32x4*)w.wo; p.Wlo = (const u32x4*)w.wo_lo; p.NRG = d / 16; p.KB = m->QD / 32;
       p.X = (const u32x4*)m->xo; p.M = batch;
-      p.h = m->h; p.gain_next = w.ffn_norm; p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.ssq_stride = stride; p.d = d;
+      p.h = m->h; p.gain_next = w.ffn_norm; p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.d = d;
       prof_mark(m, PK_OPROJ, st);
       launch_gemm<EPI_RESID>(m, p, MT, st);
       n_ssq = (d / 16 + 7) / 8;
@@ -812,7 +846,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       GemmP p = {};
       p.W = (const u32x4*)w.wgu; p.Wlo = (const u32x4*)w.wgu_lo; p.NRG = 2 * m->F / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
-      p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
+      p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.xa = (uint16_t*)m->xa; p.F = m->F;
       prof_mark(m, PK_GATEUP, st);
       launch_gemm<EPI_SWIGLU>(m, p, MT, st);
@@ -822,7 +856,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       p.W = (const u32x4*)w.wd; p.Wlo = (const u32x4*)w.wd_lo; p.NRG = d / 16; p.KB = m->Fp / 32;
       p.X = (const u32x4*)m->xa; p.M = batch;
       p.h = m->h; p.gain_next = (l + 1 < m->L) ? m->layers[l + 1].attn_norm : m->final_norm;
-      p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.ssq_stride = stride; p.d = d;
+      p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.d = d;
       prof_mark(m, PK_DOWN, st);
       launch_gemm<EPI_RESID>(m, p, MT, st);
     }
@@ -832,7 +866,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     GemmP p = {};
     p.W = (const u32x4*)m->lm_head; p.Wlo = (const u32x4*)m->lm_head_lo; p.NRG = m->V / 16; p.KB = d / 32;
     p.X = (const u32x4*)m->xq; p.M = batch;
-    p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.ssq_stride = stride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
+    p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
     p.logits = lg; p.V = m->V;
     prof_mark(m, PK_LMHEAD, st);
     launch_gemm<EPI_LOGITS>(m, p, MT, st);
