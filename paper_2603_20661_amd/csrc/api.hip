@@ -88,7 +88,7 @@ struct Plan {
   uint64_t embed, final_norm, lm_head, lm_head_lo, rope;
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
-  uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok;
+  uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_units;
   uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
   int attn_kps, attn_splits;
 };
@@ -157,6 +157,9 @@ static void make_plan(const www_config* c, Plan& p) {
   p.attn_part = take((uint64_t)s.maxB * s.Hkv * p.attn_splits * s.G * (s.hd + 4) * 4);
   p.logits = take((uint64_t)s.maxB * s.V * 4);
   p.last_tok = take((uint64_t)s.maxB * 4);
+  p.attn_units = take((uint64_t)s.maxB * p.attn_splits * 4);
+  p.argmax_val = take((uint64_t)s.maxB * 32 * 4);
+  p.argmax_idx = take((uint64_t)s.maxB * 32 * 4);
   p.hp = take((uint64_t)s.maxT * s.d * 4);
   const uint64_t Tpad = ((uint64_t)s.maxT + 255) / 256 * 256;  // packed activation buffers hold whole 256-token tiles
   p.ssq_p = take(Tpad * ((uint64_t)s.d / 256 + 1) * 4);
@@ -286,6 +289,8 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
   m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
   m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
+  m->attn_units = (int*)(ws + p.attn_units);
+  m->argmax_val = (float*)(ws + p.argmax_val); m->argmax_idx = (int*)(ws + p.argmax_idx);
   m->hp = (float*)(ws + p.hp); m->ssq_p = (float*)(ws + p.ssq_p); m->xn = (uint16_t*)(ws + p.xn); m->qp = (uint16_t*)(ws + p.qp); m->op = (uint16_t*)(ws + p.op); m->ap = (uint16_t*)(ws + p.ap);
   m->row_seq = (int*)(ws + p.row_seq); m->row_pos = (int*)(ws + p.row_pos); m->tile_seq = (int*)(ws + p.tile_seq);
   m->tile_q0 = (int*)(ws + p.tile_q0); m->meta = (int*)(ws + p.meta);

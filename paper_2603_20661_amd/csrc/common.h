@@ -116,6 +116,9 @@ struct www_model {
   uint16_t* xa;        // packed SwiGLU output feeding the down projection (K = Fp)
   float* partial;  // split-K partial tiles
   float* attn_part;
+  int* attn_units;    // [maxB * attn_splits] (sequence, split) items of this step, longest first
+  float* argmax_val;  // [maxB][32] per-slice maxima of the logits and
+  int* argmax_idx;    // their indices
   int* counters;
   float* logits_buf;  // used when the caller passes no logits buffer
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)

@@ -113,6 +113,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   constexpr int CHUNK_UNITS = KC * MTK * 128;      // 16-byte units of activations per k chunk
   constexpr int NSTG = CHUNK_UNITS / 256;
   __shared__ u32x4 lds[2][CHUNK_UNITS];
+  __shared__ float s_scale[64];
   // after the main loop the staging buffers are dead and are reused for the epilogue's small reductions
   float(*red)[64] = reinterpret_cast<float(*)[64]>(&lds[0][0]);
   volatile int* s_last = reinterpret_cast<volatile int*>(&lds[1][0]);
@@ -138,42 +139,49 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   // Inputs of the epilogue that hang off dependent loads (RMSNorm scale; position and KV block of each token) are
   // requested at kernel entry together with the first weights and activations, and only touched once that first chunk
   // has arrived, so they never put a memory round trip in front of the streaming loop.
-  // Sum of squares of token t: lane group g = lane/16 reads entries 16g .. 16g+15 of the token's row (four 16-byte
-  // loads, always in bounds; entries past n_ssq_in are masked), adds them in index order, and the four groups are
-  // combined by two cross-lane exchanges: a fixed order, so the scale is the same in every workgroup.
-  f32x4 ssq_raw[MTK][4];
+  // Sum of squares of a token: wavefront w owns token group w (every workgroup of the grid reads the same small table,
+  // so each reads it once, not once per wavefront).  Lane group g = lane/16 reads entries 16g .. 16g+15 of the token's
+  // row (four 16-byte loads, always in bounds; entries past n_ssq_in are masked), adds them in index order, and the
+  // four groups are combined by two cross-lane exchanges: a fixed order, so the scale is the same in every workgroup.
+  f32x4 ssq_raw[4];
   int pos_pre[MTK];
   int tok_c[MTK];
 #pragma unroll
   for (int tb = 0; tb < MTK; ++tb) {
     tok_c[tb] = min((tb0 + tb) * 16 + (lane & 15), p.M - 1);
     pos_pre[tb] = 0;
-    if (p.ssq_in) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        ssq_raw[tb][c] = *reinterpret_cast<const f32x4*>(p.ssq_in + (int64_t)tok_c[tb] * SSQ_TILES + (lane >> 4) * 16 + c * 4);
-    }
     if constexpr (EPI == EPI_QKV) pos_pre[tb] = p.seq_lens[tok_c[tb]] - 1;
+  }
+  if (p.ssq_in && wave < MTK) {
+    const int t = min((tb0 + wave) * 16 + (lane & 15), p.M - 1);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      ssq_raw[c] = *reinterpret_cast<const f32x4*>(p.ssq_in + (int64_t)t * SSQ_TILES + (lane >> 4) * 16 + c * 4);
   }
   float scale_pre[MTK];
   int blk_pre[MTK];
+  // before the first barrier: reduce the sums and publish the scales; table loads for the KV slots go out
   auto finish_prefetch = [&]() __attribute__((always_inline)) {
+    if (p.ssq_in && wave < MTK) {
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += ((lane >> 4) * 16 + c * 4 + e < p.n_ssq_in) ? ssq_raw[c][e] : 0.f;
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (lane < 16) s_scale[wave * 16 + lane] = rsqrtf(s * p.inv_dim + p.eps);
+    }
 #pragma unroll
     for (int tb = 0; tb < MTK; ++tb) {
-      scale_pre[tb] = 1.f;
       blk_pre[tb] = 0;
-      if (p.ssq_in) {
-        float s = 0.f;
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) s += ((lane >> 4) * 16 + c * 4 + e < p.n_ssq_in) ? ssq_raw[tb][c][e] : 0.f;
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
-        scale_pre[tb] = rsqrtf(s * p.inv_dim + p.eps);
-      }
       if constexpr (EPI == EPI_QKV) blk_pre[tb] = kv_block_id(p.table + (int64_t)tok_c[tb] * p.mbs, pos_pre[tb]);
     }
+  };
+  // after that barrier
+  auto read_scales = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int tb = 0; tb < MTK; ++tb) scale_pre[tb] = p.ssq_in ? s_scale[tb * 16 + (lane & 15)] : 1.f;
   };
 
   u32x4 wA[KC][R][WP], wB[KC][R][WP], stg[NSTG];
@@ -248,6 +256,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     store_stage(0);
     finish_prefetch();
     __syncthreads();
+    read_scales();
     int c = 0;
     for (; c + 2 < nchunks; c += 2) {
       load_stage(c + 1);
@@ -280,6 +289,8 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     __syncthreads();
   } else {
     finish_prefetch();
+    __syncthreads();
+    read_scales();
   }
 
   // accumulator layout: acc[r][tb][i] = Y^T[row][token], row = (rg0+r)*16 + (lane/16)*4 + i, token = (tb0+tb)*16 + lane%16
@@ -461,7 +472,56 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Decode attention, one wavefront per (key split, kv head, sequence).
+// Work list of the decode attention, built once per step and used by every layer: the (sequence, key split) items of
+// the batch sorted by their number of 32-key pairs, longest first (a stable counting sort, so the order is
+// reproducible).  Splits that lie wholly past a sequence's end come last.  Handing the long items out first keeps the
+// end of the attention kernel from waiting on a few long items that happened to start late.
+#define ATTN_MAX_PAIR_KEYS 33  // a split holds at most 1024 keys = 32 pairs
+__global__ __launch_bounds__(256) void attn_units_kernel(const int32_t* __restrict__ seq_lens, int batch, int kps, int nsplit,
+                                                         int32_t* __restrict__ units) {
+  __shared__ int cnt[ATTN_MAX_PAIR_KEYS][256];
+  __shared__ int base[ATTN_MAX_PAIR_KEYS];
+  const int n = batch * nsplit, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int per = (n + 255) / 256, i0 = min(n, tid * per), i1 = min(n, i0 + per);
+  const int nkeys = kps / 32 + 1;
+  auto pairs_of = [&](int i) {
+    const int b = i / nsplit, sp = i % nsplit;
+    return (min(max(seq_lens[b] - sp * kps, 0), kps) + 31) / 32;
+  };
+  for (int k = 0; k < nkeys; ++k) cnt[k][tid] = 0;
+  for (int i = i0; i < i1; ++i) cnt[pairs_of(i)][tid]++;  // a thread only touches its own column
+  __syncthreads();
+  // per key: exclusive prefix over the threads' counts (thread order = item order, which makes the sort stable)
+  for (int k = wave; k < nkeys; k += 4) {
+    const int v0 = cnt[k][lane * 4], v1 = cnt[k][lane * 4 + 1], v2 = cnt[k][lane * 4 + 2], v3 = cnt[k][lane * 4 + 3];
+    const int sum = v0 + v1 + v2 + v3;
+    int inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(inc, o);
+      if (lane >= o) inc += up;
+    }
+    const int exc = inc - sum;
+    cnt[k][lane * 4] = exc;
+    cnt[k][lane * 4 + 1] = exc + v0;
+    cnt[k][lane * 4 + 2] = exc + v0 + v1;
+    cnt[k][lane * 4 + 3] = exc + v0 + v1 + v2;
+    if (lane == 63) base[k] = inc;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int acc = 0;
+    for (int k = nkeys - 1; k >= 0; --k) { const int c = base[k]; base[k] = acc; acc += c; }
+  }
+  __syncthreads();
+  for (int i = i0; i < i1; ++i) {
+    const int k = pairs_of(i);
+    units[base[k] + cnt[k][tid]++] = i;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Decode attention, one wavefront per (key split, kv head, sequence), taken from the work list above.
 //   S^T = K Q^T (keys x heads), online softmax per head along the key axis with cross-lane shuffles,
 //   O^T = V^T P^T (head_dim x heads).  The G query heads of the group share every K/V byte.
 // Partial results (m, l, unnormalised o) of all splits of a (sequence, kv head) are merged by the
@@ -471,11 +531,15 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const uint16_t* __restr
                                                           const uint16_t* __restrict__ kplane,
                                                           const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
                                                           const int32_t* __restrict__ table, int mbs, int Hq, int Hkv, int kps,
+                                                          const int32_t* __restrict__ units, int nsplit_max,
                                                           float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
   constexpr int NKF = HD / 32;  // K fragments per block
   constexpr int NVF = HD / 16;  // V fragments per block
   constexpr int PSTRIDE = HD + 4;  // floats per (split, head) partial record: o[HD], m, l, pad
-  const int split = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+  // blockIdx.x = item * Hkv + kv head: the kv heads of one item are neighbours in launch order
+  const int j = blockIdx.x % Hkv;
+  const int item = __builtin_amdgcn_readfirstlane(units[blockIdx.x / Hkv]);
+  const int split = item % nsplit_max, b = item / nsplit_max;
   const int lane = threadIdx.x;
   const int n = lane & 15, g = lane >> 4;
   const int k0 = split * kps;
@@ -500,7 +564,6 @@ __global__ __launch_bounds__(64) void decode_attn_kernel(const uint16_t* __restr
   }
   if (k0 >= ctx) return;
   const int nsplit_act = (ctx + kps - 1) / kps;
-  const int nsplit_max = gridDim.x;
   const int kend = min(ctx, k0 + kps);
   const int npairs = (kend - k0 + 31) / 32;
   const int last_blk_local = (kend - 1) / KV_BS - blk0;  // index, within this split, of its last valid block
@@ -701,29 +764,45 @@ __global__ __launch_bounds__(64) void decode_attn_merge_kernel(const int32_t* __
 }
 
 // ------------------------------------------------------------------------------------------------
-// Greedy next token: index of the largest logit, the lowest index winning ties.
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ out) {
-  const float* row = logits + (int64_t)blockIdx.x * V;
+// Greedy next token: index of the largest logit, the lowest index winning ties.  Two stages: ARGMAX_CHUNKS
+// workgroups per row each scan a contiguous slice with 16-byte loads, then one wavefront per row combines them.
+#define ARGMAX_CHUNKS 32
+__device__ __forceinline__ void argmax_take(float& best, int& bi, float v, int i) {
+  if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+}
+__global__ __launch_bounds__(256) void argmax_partial_kernel(const float* __restrict__ logits, int V, float* __restrict__ pval,
+                                                             int* __restrict__ pidx) {
+  const float* row = logits + (int64_t)blockIdx.y * V;
+  const int nq = V / 4, per = (nq + ARGMAX_CHUNKS - 1) / ARGMAX_CHUNKS;
+  const int q0 = blockIdx.x * per, q1 = min(nq, q0 + per);
   float best = NEG_INF;
   int bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < V; i += blockDim.x) {
-    float v = row[i];
-    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  for (int q = q0 + threadIdx.x; q < q1; q += 256) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(row + 4 * q);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) argmax_take(best, bi, v[e], 4 * q + e);
   }
-  __shared__ float sv[1024];
-  __shared__ int si[1024];
-  sv[threadIdx.x] = best;
-  si[threadIdx.x] = bi;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) argmax_take(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
   __syncthreads();
-  for (int s = 512; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) {
-      float ov = sv[threadIdx.x + s];
-      int oi = si[threadIdx.x + s];
-      if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) { sv[threadIdx.x] = ov; si[threadIdx.x] = oi; }
-    }
-    __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) argmax_take(best, bi, sv[w], si[w]);
+    pval[blockIdx.y * ARGMAX_CHUNKS + blockIdx.x] = best;
+    pidx[blockIdx.y * ARGMAX_CHUNKS + blockIdx.x] = bi;
   }
-  if (threadIdx.x == 0) out[blockIdx.x] = si[0];
+}
+__global__ __launch_bounds__(64) void argmax_final_kernel(const float* __restrict__ pval, const int* __restrict__ pidx,
+                                                          int32_t* __restrict__ out) {
+  const int lane = threadIdx.x;
+  float best = lane < ARGMAX_CHUNKS ? pval[blockIdx.x * ARGMAX_CHUNKS + lane] : NEG_INF;
+  int bi = lane < ARGMAX_CHUNKS ? pidx[blockIdx.x * ARGMAX_CHUNKS + lane] : 0x7fffffff;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) argmax_take(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
+  if (lane == 0) out[blockIdx.x] = bi;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -799,6 +878,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
   else
     hipLaunchKernelGGL(embed_pack_kernel<uint16_t>, dim3(batch), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d,
                        m->layers[0].attn_norm, m->h, m->ssq, (uint16_t*)m->xq, MT);
+  hipLaunchKernelGGL(attn_units_kernel, dim3(1), dim3(256), 0, st, lens, batch, m->attn_kps, m->attn_splits, m->attn_units);
   int n_ssq = 1;
   const float qscale = 1.4426950408889634f / sqrtf((float)m->hd);
   for (int l = 0; l < m->L; ++l) {
@@ -816,12 +896,13 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       launch_gemm<EPI_QKV>(m, p, MT, st);
     }
     {
-      dim3 grid(m->attn_splits, m->Hkv, batch);
+      dim3 grid((unsigned)batch * m->attn_splits * m->Hkv);
       prof_mark(m, PK_ATTN, st);
 #define ATTN(HD_, G_)                                                                                                              \
   {                                                                                                                                \
-    hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q_hi, m->q_lo, kplane, vplane, lens, table,                     \
-                       (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, m->attn_part, (uint16_t*)m->xo, MT);     \
+    hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q_hi, m->q_lo, kplane, vplane, lens, table,          \
+                       (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, m->attn_units, m->attn_splits, m->attn_part,     \
+                       (uint16_t*)m->xo, MT);                                                                                      \
     if (m->attn_splits > 1)                                                                                                        \
       hipLaunchKernelGGL((decode_attn_merge_kernel<HD_, G_>), dim3(m->Hkv, batch), dim3(64), 0, st, lens, m->Hkv, m->attn_kps,      \
                          m->attn_splits, m->attn_part, (uint16_t*)m->xo, MT);                                                      \
@@ -872,7 +953,10 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     launch_gemm<EPI_LOGITS>(m, p, MT, st);
   }
   if (next) prof_mark(m, PK_ARGMAX, st);
-  if (next) hipLaunchKernelGGL(argmax_kernel, dim3(batch), dim3(1024), 0, st, lg, m->V, next);
+  if (next) {
+    hipLaunchKernelGGL(argmax_partial_kernel, dim3(ARGMAX_CHUNKS, batch), dim3(256), 0, st, lg, m->V, m->argmax_val, m->argmax_idx);
+    hipLaunchKernelGGL(argmax_final_kernel, dim3(batch), dim3(64), 0, st, m->argmax_val, m->argmax_idx, next);
+  }
   prof_mark(m, -1, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
