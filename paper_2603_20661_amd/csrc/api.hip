@@ -88,9 +88,9 @@ struct Plan {
   uint64_t embed, final_norm, lm_head, lm_head_lo, rope;
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
-  uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_units;
+  uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_hdr, attn_start, attn_pref;
   uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
-  int attn_kps, attn_splits;
+  int attn_maxrec;
 };
 
 struct Dims {
@@ -152,12 +152,15 @@ static void make_plan(const www_config* c, Plan& p) {
       }
   }
   p.partial = take(part ? part : 256);
-  p.attn_kps = 512;  // keys per decode-attention split (a split spans at most 64 blocks, i.e. 1024 keys)
-  p.attn_splits = (s.max_pos + p.attn_kps - 1) / p.attn_kps;
-  p.attn_part = take((uint64_t)s.maxB * s.Hkv * p.attn_splits * s.G * (s.hd + 4) * 4);
+  // a wavefront of the decode attention takes at least 16 key pairs (512 keys) of the batch's work list, so a sequence
+  // is cut into at most max_pos / 512 + 2 segments
+  p.attn_maxrec = s.max_pos / 512 + 2;
+  p.attn_part = take((uint64_t)s.maxB * s.Hkv * p.attn_maxrec * s.G * (s.hd + 4) * 4);
   p.logits = take((uint64_t)s.maxB * s.V * 4);
   p.last_tok = take((uint64_t)s.maxB * 4);
-  p.attn_units = take((uint64_t)s.maxB * p.attn_splits * 4);
+  p.attn_hdr = take(16);
+  p.attn_start = take((uint64_t)MAX_ATTN_WAVES * 16);
+  p.attn_pref = take(((uint64_t)s.maxB + 1) * 4);
   p.argmax_val = take((uint64_t)s.maxB * 32 * 4);
   p.argmax_idx = take((uint64_t)s.maxB * 32 * 4);
   p.hp = take((uint64_t)s.maxT * s.d * 4);
@@ -289,12 +292,14 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
   m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
   m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
-  m->attn_units = (int*)(ws + p.attn_units);
+  m->attn_hdr = (int*)(ws + p.attn_hdr); m->attn_start = (int*)(ws + p.attn_start); m->attn_pref = (int*)(ws + p.attn_pref);
   m->argmax_val = (float*)(ws + p.argmax_val); m->argmax_idx = (int*)(ws + p.argmax_idx);
   m->hp = (float*)(ws + p.hp); m->ssq_p = (float*)(ws + p.ssq_p); m->xn = (uint16_t*)(ws + p.xn); m->qp = (uint16_t*)(ws + p.qp); m->op = (uint16_t*)(ws + p.op); m->ap = (uint16_t*)(ws + p.ap);
   m->row_seq = (int*)(ws + p.row_seq); m->row_pos = (int*)(ws + p.row_pos); m->tile_seq = (int*)(ws + p.tile_seq);
   m->tile_q0 = (int*)(ws + p.tile_q0); m->meta = (int*)(ws + p.meta);
-  m->attn_kps = p.attn_kps; m->attn_splits = p.attn_splits;
+  m->attn_maxrec = p.attn_maxrec;
+  m->attn_waves = decode_attn_resident_waves(s.hd, s.G);
+  if (m->attn_waves > MAX_ATTN_WAVES) m->attn_waves = MAX_ATTN_WAVES;
   *out = m;
   return WWW_OK;
 }

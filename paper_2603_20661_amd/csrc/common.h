@@ -116,7 +116,7 @@ struct www_model {
   uint16_t* xa;        // packed SwiGLU output feeding the down projection (K = Fp)
   float* partial;  // split-K partial tiles
   float* attn_part;
-  int* attn_units;    // [maxB * attn_splits] (sequence, split) items of this step, longest first
+  int *attn_hdr, *attn_start, *attn_pref;  // per-step plan of the decode attention: totals, per-wavefront start, prefix of pair counts
   float* argmax_val;  // [maxB][32] per-slice maxima of the logits and
   int* argmax_idx;    // their indices
   int* counters;
@@ -130,14 +130,15 @@ struct www_model {
   uint16_t* op;        // packed [maxT][QD] attention output
   uint16_t* ap;        // packed [maxT][Fp] SwiGLU output
   int *row_seq, *row_pos, *tile_seq, *tile_q0, *meta;  // ragged-batch bookkeeping
-  int attn_kps;    // keys per decode-attention split
-  int attn_splits; // grid.x of the decode attention
+  int attn_waves;  // wavefronts of the decode attention grid (all resident at once)
+  int attn_maxrec; // most partial records per (sequence, kv head)
   GraphEntry* graphs;
   int n_graphs;
   int use_graph;
   struct DecodeProfiler* prof;  // per-kernel-class timing of eager decode steps (benchmark hook), or null
 };
 
+#define MAX_ATTN_WAVES 8192  // upper bound of the decode attention grid, in wavefronts (sizes its plan buffer)
 #define SSQ_TILES 64       // most row tiles of a residual-producing GEMM (d_model / 128)
 #define GEMM_TILE_ROWS 128 // rows of W per workgroup of the skinny GEMM
 #define MAX_KSPLIT 16
@@ -148,6 +149,7 @@ void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in f
 
 // host-side launchers (decode.hip / prefill.hip / pack.hip)
 void set_error(const char* fmt, ...);
+int decode_attn_resident_waves(int hd, int G);
 int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int32_t* table, int batch, float* logits, int32_t* next,
                hipStream_t st);
 int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const int32_t* lens, const int32_t* table, int batch, int T,

@@ -472,242 +472,271 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Work list of the decode attention, built once per step and used by every layer: the (sequence, key split) items of
-// the batch sorted by their number of 32-key pairs, longest first (a stable counting sort, so the order is
-// reproducible).  Splits that lie wholly past a sequence's end come last.  Handing the long items out first keeps the
-// end of the attention kernel from waiting on a few long items that happened to start late.
-#define ATTN_MAX_PAIR_KEYS 33  // a split holds at most 1024 keys = 32 pairs
-__global__ __launch_bounds__(256) void attn_units_kernel(const int32_t* __restrict__ seq_lens, int batch, int kps, int nsplit,
-                                                         int32_t* __restrict__ units) {
-  __shared__ int cnt[ATTN_MAX_PAIR_KEYS][256];
-  __shared__ int base[ATTN_MAX_PAIR_KEYS];
-  const int n = batch * nsplit, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int per = (n + 255) / 256, i0 = min(n, tid * per), i1 = min(n, i0 + per);
-  const int nkeys = kps / 32 + 1;
-  auto pairs_of = [&](int i) {
-    const int b = i / nsplit, sp = i % nsplit;
-    return (min(max(seq_lens[b] - sp * kps, 0), kps) + 31) / 32;
-  };
-  for (int k = 0; k < nkeys; ++k) cnt[k][tid] = 0;
-  for (int i = i0; i < i1; ++i) cnt[pairs_of(i)][tid]++;  // a thread only touches its own column
-  __syncthreads();
-  // per key: exclusive prefix over the threads' counts (thread order = item order, which makes the sort stable)
-  for (int k = wave; k < nkeys; k += 4) {
-    const int v0 = cnt[k][lane * 4], v1 = cnt[k][lane * 4 + 1], v2 = cnt[k][lane * 4 + 2], v3 = cnt[k][lane * 4 + 3];
-    const int sum = v0 + v1 + v2 + v3;
-    int inc = sum;
+// Plan of the decode attention, built once per step and used by every layer.
+//
+// The keys of the batch are counted in pairs of 16-key blocks.  All (sequence b, kv head j, pair) triples, in that
+// order, form one long list of T = Hkv * sum_b P_b entries (P_b = pairs of sequence b); the attention kernel runs W
+// wavefronts and wavefront w takes the entries [w*C, (w+1)*C), C = max(16, ceil(T / W)).  Every wavefront therefore
+// streams the same number of bytes and all of them finish together, whatever the mix of sequence lengths.  A chunk may
+// end inside a (b, j) sequence and continue into the next one; each piece is a segment with its own softmax state,
+// parked as a record and merged afterwards (a sequence of P pairs is cut into at most P/C + 2 <= P/16 + 2 segments).
+// The cut points depend on the lengths of all sequences of the batch: results are reproducible for a given batch
+// but the rounding of a sequence's attention output may differ between batches of different composition.
+//   hdr[0] = T, hdr[1] = C;  start[w] = (b, j, first pair) of wavefront w, b = -1 if it has no work;
+//   pref[b] = sum of P over the sequences before b
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restrict__ seq_lens, int batch, int Hkv, int W,
+                                                        int32_t* __restrict__ hdr, int32_t* __restrict__ start,
+                                                        int32_t* __restrict__ pref_out) {
+  extern __shared__ int pref[];  // [batch + 1]
+  const int tid = threadIdx.x, lane = tid & 63;
+  if (tid < 64) {
+    int carry = 0;
+    if (lane == 0) pref[0] = 0;
+    for (int c = 0; c < batch; c += 64) {
+      const int bb = c + lane;
+      const int P = bb < batch ? max(0, (seq_lens[bb] + 31) / 32) : 0;
+      int inc = P;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int up = __shfl_up(inc, o);
-      if (lane >= o) inc += up;
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+      }
+      if (bb < batch) pref[bb + 1] = carry + inc;
+      carry += __shfl(inc, 63);
     }
-    const int exc = inc - sum;
-    cnt[k][lane * 4] = exc;
-    cnt[k][lane * 4 + 1] = exc + v0;
-    cnt[k][lane * 4 + 2] = exc + v0 + v1;
-    cnt[k][lane * 4 + 3] = exc + v0 + v1 + v2;
-    if (lane == 63) base[k] = inc;
   }
   __syncthreads();
-  if (tid == 0) {
-    int acc = 0;
-    for (int k = nkeys - 1; k >= 0; --k) { const int c = base[k]; base[k] = acc; acc += c; }
-  }
-  __syncthreads();
-  for (int i = i0; i < i1; ++i) {
-    const int k = pairs_of(i);
-    units[base[k] + cnt[k][tid]++] = i;
+  const int T = pref[batch] * Hkv;
+  const int C = max(16, (T + W - 1) / W);
+  if (tid == 0) { hdr[0] = T; hdr[1] = C; }
+  for (int i = tid; i <= batch; i += 256) pref_out[i] = pref[i];
+  for (int w = tid; w < W; w += 256) {
+    const int64_t x0 = (int64_t)w * C;
+    int sb = -1, sj = 0, sp = 0;
+    if (x0 < T) {
+      int lo = 0, hi = batch - 1;  // largest b with Hkv * pref[b] <= x0
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)pref[mid] * Hkv <= x0) lo = mid; else hi = mid - 1;
+      }
+      const int P = pref[lo + 1] - pref[lo];
+      const int r = (int)(x0 - (int64_t)pref[lo] * Hkv);
+      sb = lo; sj = r / P; sp = r % P;
+    }
+    start[4 * w] = sb; start[4 * w + 1] = sj; start[4 * w + 2] = sp; start[4 * w + 3] = 0;
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Decode attention, one wavefront per (key split, kv head, sequence), taken from the work list above.
+// Decode attention.  Each wavefront walks its chunk of the plan above, segment by segment:
 //   S^T = K Q^T (keys x heads), online softmax per head along the key axis with cross-lane shuffles,
 //   O^T = V^T P^T (head_dim x heads).  The G query heads of the group share every K/V byte.
-// Partial results (m, l, unnormalised o) of all splits of a (sequence, kv head) are merged by the
-// wavefront that finishes last, which also writes the packed hi/lo operand of the O projection.
+// A segment that covers its whole (sequence, kv head) writes the packed hi/lo operand of the O projection itself;
+// otherwise it parks (m, l, unnormalised o) as record number (w - first wavefront of that sequence).
 template <int HD, int G>
-__global__ __launch_bounds__(64) void decode_attn_kernel(const uint16_t* __restrict__ q_hi, const uint16_t* __restrict__ q_lo,
-                                                          const uint16_t* __restrict__ kplane,
-                                                          const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
-                                                          const int32_t* __restrict__ table, int mbs, int Hq, int Hkv, int kps,
-                                                          const int32_t* __restrict__ units, int nsplit_max,
-                                                          float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
+__global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __restrict__ q_hi, const uint16_t* __restrict__ q_lo,
+                                                           const uint16_t* __restrict__ kplane,
+                                                           const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
+                                                           const int32_t* __restrict__ table, int batch, int mbs, int Hq, int Hkv,
+                                                           const int32_t* __restrict__ hdr, const int32_t* __restrict__ start,
+                                                           int maxrec, float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
   constexpr int NKF = HD / 32;  // K fragments per block
   constexpr int NVF = HD / 16;  // V fragments per block
-  constexpr int PSTRIDE = HD + 4;  // floats per (split, head) partial record: o[HD], m, l, pad
-  // blockIdx.x = item * Hkv + kv head: the kv heads of one item are neighbours in launch order
-  const int j = blockIdx.x % Hkv;
-  const int item = __builtin_amdgcn_readfirstlane(units[blockIdx.x / Hkv]);
-  const int split = item % nsplit_max, b = item / nsplit_max;
-  const int lane = threadIdx.x;
+  constexpr int PSTRIDE = HD + 4;  // floats per (record, head): o[HD], m, l, pad
+  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   const int n = lane & 15, g = lane >> 4;
-  const int k0 = split * kps;
-  const int32_t* trow = table + (int64_t)b * mbs;
-  // block ids of this split, one per lane (a split spans at most 64 blocks); independent of the sequence length so that
-  // this load, the length and the queries are all in flight together.  Entries past the sequence's last block are unused.
-  const int blk0 = k0 / KV_BS;
-  const int my_blk = trow[min(blk0 + lane, mbs - 1)];
-  const int ctx = __builtin_amdgcn_readfirstlane(seq_lens[b]);  // wave-uniform: keeps loop bounds and lane selects scalar
-  // Q^T operand: lane (head n, group g) holds dims f*32 + g*8 .. +7 of head n, as fp16 hi + lo (pre-scaled by the producer)
-  f16x8 qhi[NKF], qlo[NKF];
-  {
-    const int64_t qoff = ((int64_t)b * Hq + j * G + min(n, G - 1)) * HD + g * 8;
-#pragma unroll
-    for (int f = 0; f < NKF; ++f) {
-      u32x4 h = *reinterpret_cast<const u32x4*>(q_hi + qoff + f * 32);
-      u32x4 l = *reinterpret_cast<const u32x4*>(q_lo + qoff + f * 32);
-      if (n >= G) { h = u32x4{0, 0, 0, 0}; l = u32x4{0, 0, 0, 0}; }
-      qhi[f] = as_f16x8(h);
-      qlo[f] = as_f16x8(l);
-    }
-  }
-  if (k0 >= ctx) return;
-  const int nsplit_act = (ctx + kps - 1) / kps;
-  const int kend = min(ctx, k0 + kps);
-  const int npairs = (kend - k0 + 31) / 32;
-  const int last_blk_local = (kend - 1) / KV_BS - blk0;  // index, within this split, of its last valid block
-
-  f32x4 oacc[NVF];
-#pragma unroll
-  for (int f = 0; f < NVF; ++f) oacc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_INF, l_run = 0.f;
-
+  const int T = hdr[0], C = hdr[1];
+  int b = __builtin_amdgcn_readfirstlane(start[4 * w]);
+  if (b < 0) return;
+  int j = __builtin_amdgcn_readfirstlane(start[4 * w + 1]);
+  int p = __builtin_amdgcn_readfirstlane(start[4 * w + 2]);
+  int x = w * C;                      // position in the list of the next entry
+  int remaining = min(C, T - x);
   const int64_t blk_elems = (int64_t)KV_BS * HD;
 
-  struct KV {
-    u32x4 k0[NKF], k1[NKF];
-    u32x2 v0[NVF], v1[NVF];
-  };
-  auto load_pair = [&](KV& r, int pr) __attribute__((always_inline)) {
-    const int id0 = __shfl(my_blk, min(2 * pr, last_blk_local));
-    const int id1 = __shfl(my_blk, min(2 * pr + 1, last_blk_local));  // past the end: the last block again (masked)
-    const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
-    const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
-#pragma unroll
-    for (int f = 0; f < NKF; ++f) {
-      r.k0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
-      r.k1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
+  while (remaining > 0 && b < batch) {  // (the second test only guards against a plan that does not match the lengths)
+    const int ctx = __builtin_amdgcn_readfirstlane(seq_lens[b]);
+    const int P = (ctx + 31) / 32;
+    if (P <= 0) {  // an empty sequence has no entries in the list
+      ++b;
+      continue;
     }
+    const int np = min(P - p, remaining);
+    const int kend = min(ctx, (p + np) * 32);
+    const int32_t* trow = table + (int64_t)b * mbs;
+    // Q^T operand: lane (head n, group g) holds dims f*32 + g*8 .. +7 of head n, as fp16 hi + lo (pre-scaled by the producer)
+    f16x8 qhi[NKF], qlo[NKF];
+    {
+      const int64_t qoff = ((int64_t)b * Hq + j * G + min(n, G - 1)) * HD + g * 8;
 #pragma unroll
-    for (int f = 0; f < NVF; ++f) {
-      r.v0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
-      r.v1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
-    }
-  };
-  auto process = [&](KV& r, int pr) __attribute__((always_inline)) {
-    const int base = k0 + pr * 32;
-    // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1)
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int f = 0; f < NKF; ++f) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qhi[f], s0, 0, 0, 0);
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qlo[f], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qhi[f], s1, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qlo[f], s1, 0, 0, 0);
-    }
-    float sc[8];
-    float mx = NEG_INF;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      sc[i] = (base + 4 * g + i < kend) ? s0[i] : NEG_INF;
-      sc[4 + i] = (base + 16 + 4 * g + i < kend) ? s1[i] : NEG_INF;
-      mx = fmaxf(mx, fmaxf(sc[i], sc[4 + i]));
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    union { uint16_t s[8]; f16x8 v; } pb;
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float pv = __builtin_amdgcn_exp2f(sc[i] - m_new);
-      psum += pv;
-      pb.s[i] = f32_to_f16_sat(pv);
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    // values of masked keys must not reach the MFMA (0 * NaN): clear them.  Done for every pair, without a branch:
-    // the masks are all-ones except in a split's last pair.
-    const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
-    const uint32_t a01 = (ka + 0 < kend ? 0xFFFFu : 0u) | (ka + 1 < kend ? 0xFFFF0000u : 0u);
-    const uint32_t a23 = (ka + 2 < kend ? 0xFFFFu : 0u) | (ka + 3 < kend ? 0xFFFF0000u : 0u);
-    const uint32_t b01 = (kb2 + 0 < kend ? 0xFFFFu : 0u) | (kb2 + 1 < kend ? 0xFFFF0000u : 0u);
-    const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
-#pragma unroll
-    for (int f = 0; f < NVF; ++f) {
-      const u32x4 a = {r.v0[f].x & a01, r.v0[f].y & a23, r.v1[f].x & b01, r.v1[f].y & b23};
-      oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
-      oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
-    }
-  };
-
-  // two register sets: the keys and values of pair pr+1 travel while pair pr is processed
-  KV ra, rb;
-  load_pair(ra, 0);
-  int pr = 0;
-  bool done = false;
-  while (pr + 1 < npairs) {
-    load_pair(rb, pr + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    process(ra, pr);
-    ++pr;
-    if (pr + 1 >= npairs) {
-      process(rb, pr);
-      done = true;
-      break;
-    }
-    load_pair(ra, pr + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    process(rb, pr);
-    ++pr;
-  }
-  if (!done) process(ra, pr);
-
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-
-  if (nsplit_act == 1) {
-    // the whole context fitted into this split: normalise and emit the packed O-projection operand directly
-    if (n < G) {
-      const float inv = 1.f / l_run;
-#pragma unroll
-      for (int f = 0; f < NVF; ++f) {
-        union { uint16_t s[4]; u32x2 v; } hi, lo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) split_f16(oacc[f][i] * inv, hi.s[i], lo.s[i]);
-        const int k = (j * G + n) * HD + f * 16 + g * 4;
-        *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 0)) = hi.v;
-        *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 1)) = lo.v;
+      for (int f = 0; f < NKF; ++f) {
+        u32x4 h = *reinterpret_cast<const u32x4*>(q_hi + qoff + f * 32);
+        u32x4 l = *reinterpret_cast<const u32x4*>(q_lo + qoff + f * 32);
+        if (n >= G) { h = u32x4{0, 0, 0, 0}; l = u32x4{0, 0, 0, 0}; }
+        qhi[f] = as_f16x8(h);
+        qlo[f] = as_f16x8(l);
       }
     }
-    return;
-  }
-
-  // park this split's record [b][j][split][head n][o(HD), m, l]; a separate small kernel merges the records of
-  // split sequences (a kernel boundary is a far cheaper hand-over here than in-kernel device-scope signalling)
-  float* rec = part + ((((int64_t)b * Hkv + j) * nsplit_max + split) * G) * PSTRIDE;
-  if (n < G) {
+    f32x4 oacc[NVF];
 #pragma unroll
-    for (int f = 0; f < NVF; ++f)
-      *reinterpret_cast<float4*>(rec + n * PSTRIDE + f * 16 + g * 4) = make_float4(oacc[f][0], oacc[f][1], oacc[f][2], oacc[f][3]);
-    if (g == 0) {
-      rec[n * PSTRIDE + HD] = m_run;
-      rec[n * PSTRIDE + HD + 1] = l_run;
+    for (int f = 0; f < NVF; ++f) oacc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = NEG_INF, l_run = 0.f;
+
+    // the segment in runs of at most 32 pairs = 64 blocks, whose ids are held one per lane
+    for (int sp = 0; sp < np; sp += 32) {
+      const int npairs = min(32, np - sp);
+      const int k0 = (p + sp) * 32;
+      const int blk0 = k0 / KV_BS;
+      const int my_blk = trow[min(blk0 + lane, mbs - 1)];
+      const int last_blk_local = min(63, (kend - 1) / KV_BS - blk0);  // index, within this run, of its last valid block
+
+      struct KV {
+        u32x4 k0[NKF], k1[NKF];
+        u32x2 v0[NVF], v1[NVF];
+      };
+      auto load_pair = [&](KV& r, int pr) __attribute__((always_inline)) {
+        const int id0 = __shfl(my_blk, min(2 * pr, last_blk_local));
+        const int id1 = __shfl(my_blk, min(2 * pr + 1, last_blk_local));  // past the end: the last block again (masked)
+        const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
+        const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
+#pragma unroll
+        for (int f = 0; f < NKF; ++f) {
+          r.k0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
+          r.k1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
+        }
+#pragma unroll
+        for (int f = 0; f < NVF; ++f) {
+          r.v0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
+          r.v1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
+        }
+      };
+      auto process = [&](KV& r, int pr) __attribute__((always_inline)) {
+        const int base = k0 + pr * 32;
+        // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1)
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int f = 0; f < NKF; ++f) {
+          s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qhi[f], s0, 0, 0, 0);
+          s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qlo[f], s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qhi[f], s1, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qlo[f], s1, 0, 0, 0);
+        }
+        float sc[8];
+        float mx = NEG_INF;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sc[i] = (base + 4 * g + i < kend) ? s0[i] : NEG_INF;
+          sc[4 + i] = (base + 16 + 4 * g + i < kend) ? s1[i] : NEG_INF;
+          mx = fmaxf(mx, fmaxf(sc[i], sc[4 + i]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        union { uint16_t s[8]; f16x8 v; } pb;
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float pv = __builtin_amdgcn_exp2f(sc[i] - m_new);
+          psum += pv;
+          pb.s[i] = f32_to_f16_sat(pv);
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        // values of masked keys must not reach the MFMA (0 * NaN): clear them.  Done for every pair, without a branch:
+        // the masks are all-ones except in a sequence's last pair.
+        const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
+        const uint32_t a01 = (ka + 0 < kend ? 0xFFFFu : 0u) | (ka + 1 < kend ? 0xFFFF0000u : 0u);
+        const uint32_t a23 = (ka + 2 < kend ? 0xFFFFu : 0u) | (ka + 3 < kend ? 0xFFFF0000u : 0u);
+        const uint32_t b01 = (kb2 + 0 < kend ? 0xFFFFu : 0u) | (kb2 + 1 < kend ? 0xFFFF0000u : 0u);
+        const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
+#pragma unroll
+        for (int f = 0; f < NVF; ++f) {
+          const u32x4 a = {r.v0[f].x & a01, r.v0[f].y & a23, r.v1[f].x & b01, r.v1[f].y & b23};
+          oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
+          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
+        }
+      };
+
+      // two register sets: the keys and values of pair pr+1 travel while pair pr is processed
+      KV ra, rb;
+      load_pair(ra, 0);
+      int pr = 0;
+      bool done = false;
+      while (pr + 1 < npairs) {
+        load_pair(rb, pr + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        process(ra, pr);
+        ++pr;
+        if (pr + 1 >= npairs) {
+          process(rb, pr);
+          done = true;
+          break;
+        }
+        load_pair(ra, pr + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        process(rb, pr);
+        ++pr;
+      }
+      if (!done) process(ra, pr);
     }
+
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+
+    const int S = x - p;                // list position of this (b, j) sequence's first pair
+    const int first_w = S / C;
+    const int nrec = (S + P - 1) / C - first_w + 1;
+    if (nrec == 1) {
+      // this segment is the whole sequence: normalise and emit the packed O-projection operand directly
+      if (n < G) {
+        const float inv = 1.f / l_run;
+#pragma unroll
+        for (int f = 0; f < NVF; ++f) {
+          union { uint16_t s[4]; u32x2 v; } hi, lo;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) split_f16(oacc[f][i] * inv, hi.s[i], lo.s[i]);
+          const int k = (j * G + n) * HD + f * 16 + g * 4;
+          *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 0)) = hi.v;
+          *reinterpret_cast<u32x2*>(xo + packed_x_offset(k, b, MT, 1)) = lo.v;
+        }
+      }
+    } else {
+      // park the record [b][j][w - first_w][head n][o(HD), m, l]; a separate small kernel merges the records (a kernel
+      // boundary is a far cheaper hand-over here than in-kernel device-scope signalling)
+      float* rec = part + ((((int64_t)b * Hkv + j) * maxrec + (w - first_w)) * G) * PSTRIDE;
+      if (n < G) {
+#pragma unroll
+        for (int f = 0; f < NVF; ++f)
+          *reinterpret_cast<float4*>(rec + n * PSTRIDE + f * 16 + g * 4) = make_float4(oacc[f][0], oacc[f][1], oacc[f][2], oacc[f][3]);
+        if (g == 0) {
+          rec[n * PSTRIDE + HD] = m_run;
+          rec[n * PSTRIDE + HD + 1] = l_run;
+        }
+      }
+    }
+    x += np;
+    remaining -= np;
+    p = 0;
+    if (++j == Hkv) { j = 0; ++b; }
   }
 }
 
-// Merges the split records of one (sequence, kv head) in split order and writes the packed hi/lo operand of the O
-// projection.  One wavefront per (kv head, sequence); sequences that fitted into one split were finished by the
+// Merges the records of one (sequence, kv head) in key order and writes the packed hi/lo operand of the O
+// projection.  One wavefront per (kv head, sequence); sequences that were a single segment were finished by the
 // attention kernel itself.
 template <int HD, int G>
-__global__ __launch_bounds__(64) void decode_attn_merge_kernel(const int32_t* __restrict__ seq_lens, int Hkv, int kps, int nsplit_max,
-                                                                const float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
+__global__ __launch_bounds__(64) void decode_attn_merge_kernel(const int32_t* __restrict__ seq_lens, int Hkv,
+                                                                const int32_t* __restrict__ hdr, const int32_t* __restrict__ pref,
+                                                                int nsplit_max, const float* __restrict__ part,
+                                                                uint16_t* __restrict__ xo, int MT) {
   constexpr int PSTRIDE = HD + 4;
   const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-  const int nsplit_act = (seq_lens[b] + kps - 1) / kps;
+  const int C = hdr[1];
+  const int P = max(0, (seq_lens[b] + 31) / 32);
+  const int S = pref[b] * Hkv + j * P;  // list position of this sequence's first pair
+  const int nsplit_act = (S + P - 1) / C - S / C + 1;
   if (nsplit_act <= 1) return;
   // Lane owns head-dim elements lane + 64*i of every head; records are read four splits at a time so the merge is
   // not one memory round trip per split.
@@ -865,6 +894,25 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
 #undef LAUNCH
 }
 
+// wavefronts the decode attention kernel keeps resident on the whole device (its grid), a multiple of 4
+int decode_attn_resident_waves(int hd, int G) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 1024;
+  }
+  hipError_t e = hipErrorInvalidValue;
+#define OCC(HD_, G_) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_kernel<HD_, G_>, 256, 0)
+  if (hd == 128) {
+    if (G == 1) OCC(128, 1); else if (G == 2) OCC(128, 2); else if (G == 4) OCC(128, 4); else OCC(128, 8);
+  } else {
+    if (G == 1) OCC(64, 1); else if (G == 2) OCC(64, 2); else if (G == 4) OCC(64, 4); else OCC(64, 8);
+  }
+#undef OCC
+  if (e != hipSuccess || per_cu < 1) { (void)hipGetLastError(); per_cu = 1; }
+  return per_cu * cus * 4;
+}
+
 int decode_MT(int batch) { return batch <= 16 ? 1 : batch <= 32 ? 2 : ((batch + 63) / 64) * 4; }
 
 int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int32_t* table, int batch, float* logits, int32_t* next,
@@ -878,7 +926,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
   else
     hipLaunchKernelGGL(embed_pack_kernel<uint16_t>, dim3(batch), dim3(256), 0, st, tok, (const uint16_t*)m->embed, d,
                        m->layers[0].attn_norm, m->h, m->ssq, (uint16_t*)m->xq, MT);
-  hipLaunchKernelGGL(attn_units_kernel, dim3(1), dim3(256), 0, st, lens, batch, m->attn_kps, m->attn_splits, m->attn_units);
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), (size_t)(batch + 1) * 4, st, lens, batch, m->Hkv, m->attn_waves, m->attn_hdr,
+                     m->attn_start, m->attn_pref);
   int n_ssq = 1;
   const float qscale = 1.4426950408889634f / sqrtf((float)m->hd);
   for (int l = 0; l < m->L; ++l) {
@@ -896,16 +945,15 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       launch_gemm<EPI_QKV>(m, p, MT, st);
     }
     {
-      dim3 grid((unsigned)batch * m->attn_splits * m->Hkv);
       prof_mark(m, PK_ATTN, st);
 #define ATTN(HD_, G_)                                                                                                              \
   {                                                                                                                                \
-    hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), grid, dim3(64), 0, st, m->q_hi, m->q_lo, kplane, vplane, lens, table,          \
-                       (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_kps, m->attn_units, m->attn_splits, m->attn_part,     \
-                       (uint16_t*)m->xo, MT);                                                                                      \
-    if (m->attn_splits > 1)                                                                                                        \
-      hipLaunchKernelGGL((decode_attn_merge_kernel<HD_, G_>), dim3(m->Hkv, batch), dim3(64), 0, st, lens, m->Hkv, m->attn_kps,      \
-                         m->attn_splits, m->attn_part, (uint16_t*)m->xo, MT);                                                      \
+    hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), dim3(m->attn_waves / 4), dim3(256), 0, st, m->q_hi, m->q_lo, kplane, vplane,  \
+                       lens, table, batch, (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_hdr, m->attn_start,            \
+                       m->attn_maxrec,                                                                                             \
+                       m->attn_part, (uint16_t*)m->xo, MT);                                                                        \
+    hipLaunchKernelGGL((decode_attn_merge_kernel<HD_, G_>), dim3(m->Hkv, batch), dim3(64), 0, st, lens, m->Hkv, m->attn_hdr,        \
+                       m->attn_pref, m->attn_maxrec, m->attn_part, (uint16_t*)m->xo, MT);                                          \
   }
       if (m->hd == 128) {
         if (m->G == 1) ATTN(128, 1) else if (m->G == 2) ATTN(128, 2) else if (m->G == 4) ATTN(128, 4) else ATTN(128, 8)
