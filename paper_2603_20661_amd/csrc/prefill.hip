@@ -159,59 +159,85 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     srcA[i] = p.W + (int64_t)min(rg_tile + f, p.NRG - 1) * 64 + lane;
     srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64 + lane;
   }
-  u32x4 sa[4], sb[4];
-  auto load_stage = [&](int kb) __attribute__((always_inline)) {
+  // Two register sets carry the global loads of the next two k blocks; two fragment sets carry the LDS reads of the
+  // two 16-column halves of a k block.  Schedule of k block s (stage buffer s & 1):
+  //   request k block s+2 from memory                                  -> register set s & 1
+  //   read the fragments of half 1 of block s from LDS                  -> fragment set 1
+  //   16 MFMAs of half 0 (fragment set 0), with the copy of block s+1 (register set (s+1) & 1) into the other stage buffer
+  //   barrier that waits for LDS traffic only (the requests to memory stay in flight across it)
+  //   read the fragments of half 0 of block s+1                         -> fragment set 0
+  //   16 MFMAs of half 1 (fragment set 1)
+  // so every LDS read, LDS write and memory request is issued at least 16 MFMAs before its data is needed.
+  // Past the last k block the requests are redirected to the last block and their copies are never read.
+  u32x4 ga0[4], gb0[4], ga1[4], gb1[4];
+  u32x4 fa0[4], fb0[4], fa1[4], fb1[4];
+  const int fm = lane & 31, fh = lane >> 5;
+  auto request = [&](u32x4(&ga)[4], u32x4(&gb)[4], int kb) __attribute__((always_inline)) {
+    const int kbc = min(kb, p.KB - 1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      sa[i] = srcA[i][(int64_t)kb * p.NRG * 64];
-      sb[i] = srcB[i][(int64_t)kb * 128];
+      ga[i] = srcA[i][(int64_t)kbc * p.NRG * 64];
+      gb[i] = srcB[i][(int64_t)kbc * 128];
     }
   };
-  auto store_stage = [&](int buf) __attribute__((always_inline)) {
+  auto copy_in = [&](u32x4(&ga)[4], u32x4(&gb)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      smem[buf][(wave + 4 * i) * 64 + lane] = sa[i];
-      smem[buf][1024 + (wave + 4 * i) * 64 + lane] = sb[i];
+      smem[buf][(wave + 4 * i) * 64 + lane] = ga[i];
+      smem[buf][1024 + (wave + 4 * i) * 64 + lane] = gb[i];
     }
   };
-  // Operand fragments of the second 16-column step are fetched from LDS while the MFMAs of the first run.
-  auto compute = [&](int buf) __attribute__((always_inline)) {
+  auto fetch = [&](u32x4(&fa)[4], u32x4(&fb)[4], int buf, int k16) __attribute__((always_inline)) {
     const u32x4* A = smem[buf];
     const u32x4* B = smem[buf] + 1024;
-    const int m = lane & 31, hh = lane >> 5;
-    u32x4 af[2][4], bfr[2][4];
-    auto fetch = [&](int set, int k16) __attribute__((always_inline)) {
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) af[set][rb] = A[(wn * 8 + rb * 2 + (m >> 4)) * 64 + ((k16 * 2 + hh) << 4) + (m & 15)];
+    for (int rb = 0; rb < 4; ++rb) fa[rb] = A[(wn * 8 + rb * 2 + (fm >> 4)) * 64 + ((k16 * 2 + fh) << 4) + (fm & 15)];
 #pragma unroll
-      for (int tb = 0; tb < 4; ++tb) bfr[set][tb] = B[((wt * 4 + tb) * 2 + k16) * 64 + lane];
-    };
-    fetch(0, 0);
-    fetch(1, 1);
+    for (int tb = 0; tb < 4; ++tb) fb[tb] = B[((wt * 4 + tb) * 2 + k16) * 64 + lane];
+  };
+  auto mfma_rows = [&](u32x4(&fa)[4], u32x4(&fb)[4], int rb0, int rb1) __attribute__((always_inline)) {
+#pragma unroll
+    for (int rb = rb0; rb < rb1; ++rb)
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb)
+        acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fa[rb]), as_f16x8(fb[tb]), acc[rb][tb], 0, 0, 0);
+  };
+  auto lds_barrier = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
+  auto k_block = [&](u32x4(&ga_new)[4], u32x4(&gb_new)[4], u32x4(&ga_next)[4], u32x4(&gb_next)[4], int s) __attribute__((always_inline)) {
+    const int buf = s & 1;
+    request(ga_new, gb_new, s + 2);
+    fetch(fa1, fb1, buf, 1);
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int k16 = 0; k16 < 2; ++k16) {
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
-          acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(af[k16][rb]), as_f16x8(bfr[k16][tb]), acc[rb][tb], 0, 0, 0);
-    }
+    mfma_rows(fa0, fb0, 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    copy_in(ga_next, gb_next, buf ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(fa0, fb0, 2, 4);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+    fetch(fa0, fb0, buf ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(fa1, fb1, 0, 4);
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  // software pipeline over k blocks: the loads of block s+1 are in flight while block s is multiplied
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
-  for (int s = 0; s + 1 < p.KB; ++s) {
-    load_stage(s + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(s & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    store_stage((s + 1) & 1);
-    __syncthreads();
+  request(ga0, gb0, 0);
+  request(ga1, gb1, 1);
+  copy_in(ga0, gb0, 0);
+  lds_barrier();
+  fetch(fa0, fb0, 0, 0);
+  {
+    int s = 0;
+    for (; s + 1 < p.KB; s += 2) {
+      k_block(ga0, gb0, ga1, gb1, s);      // even block: new requests into set 0, set 1 (block s+1) goes to LDS
+      k_block(ga1, gb1, ga0, gb0, s + 1);  // odd block: the other way round
+    }
+    if (s < p.KB) k_block(ga0, gb0, ga1, gb1, s);
   }
-  compute((p.KB - 1) & 1);
   __syncthreads();  // the staging buffers are dead from here on; the residual epilogue reuses them
   float(*red_ssq)[256] = reinterpret_cast<float(*)[256]>(&smem[0][0]);
   (void)red_ssq;
