@@ -207,21 +207,36 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   };
+  // sched_group_barrier masks: 0x008 MFMA, 0x020 memory read, 0x100 LDS read, 0x200 LDS write
   auto k_block = [&](u32x4(&ga_new)[4], u32x4(&gb_new)[4], u32x4(&ga_next)[4], u32x4(&gb_next)[4], int s) __attribute__((always_inline)) {
     const int buf = s & 1;
     request(ga_new, gb_new, s + 2);
     fetch(fa1, fb1, buf, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(fa0, fb0, 0, 2);
-    __builtin_amdgcn_sched_barrier(0);
     copy_in(ga_next, gb_next, buf ^ 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(fa0, fb0, 2, 4);
+    mfma_rows(fa0, fb0, 0, 4);
+    // issue order: one LDS read and one memory request behind each of the first 8 MFMAs, one LDS write behind
+    // each of the last 8, so the matrix pipe never waits for a block of other instructions to issue
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
     __builtin_amdgcn_sched_barrier(0);
     lds_barrier();
     fetch(fa0, fb0, buf ^ 1, 0);
-    __builtin_amdgcn_sched_barrier(0);
     mfma_rows(fa1, fb1, 0, 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     __builtin_amdgcn_sched_barrier(0);
   };
 
