@@ -28,6 +28,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
 
 
@@ -125,6 +126,14 @@ def main():
         cur_tok = torch.empty(Bn, dtype=torch.int32, device=dev)
         logits = torch.empty((Bn, shape.vocab), dtype=torch.float32, device=dev)
         ev = lambda: torch.cuda.Event(enable_timing=True)
+        # a plain device copy of known size, outside the timed region: under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
+        # its counter reading calibrates the counters of the library's kernels (bytes per counter unit)
+        calib_src = torch.empty(CALIB_COPY_BYTES, dtype=torch.uint8, device=dev)
+        calib_dst = torch.empty_like(calib_src)
+        calib_src.fill_(1)
+        calib_dst.copy_(calib_src)
+        stream.synchronize()
+        del calib_src, calib_dst
 
         def one_pass(timed):
             e0, e1, e2 = ev(), ev(), ev()

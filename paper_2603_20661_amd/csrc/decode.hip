@@ -81,8 +81,9 @@ struct GemmP {
   const u32x4* X;    // packed activations
   int MT, M;         // token groups in X, valid tokens
   int kb_per_split, ksplit;
-  float* partial;    // [ksplit][MT*16][NRG*16]
-  int* counters;     // [gridDim.z][gridDim.x]
+  int row_tiles, zbs;  // grid: row_tiles * ksplit * zbs workgroups
+  float* partial;    // [ksplit][zbs][row_tiles] tiles of 128 rows x 64 tokens
+  int* counters;     // [zbs][row_tiles]
   const float* ssq_in;  // [token][SSQ_TILES]; row scale = rsqrt(sum of the first n_ssq_in entries / dim + eps); null: no scale
   int n_ssq_in;
   float inv_dim, eps;
@@ -119,7 +120,15 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   volatile int* s_last = reinterpret_cast<volatile int*>(&lds[1][0]);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int tile = blockIdx.x, split = blockIdx.y, zb = blockIdx.z;
+  // Work items are numbered split-major, item = (zb * ksplit + split) * row_tiles + tile.  Consecutive workgroup ids
+  // are dealt round-robin to the 8 XCDs, each with its own L2; handing every XCD a contiguous run of items means that
+  // the workgroups behind one L2 share one or two k ranges, so that L2 fetches only that slice of the activations.
+  int item = blockIdx.x;
+  {
+    const int n_items = gridDim.x;
+    if (n_items % 8 == 0) item = (item % 8) * (n_items / 8) + item / 8;
+  }
+  const int tile = item % p.row_tiles, split = (item / p.row_tiles) % p.ksplit, zb = item / (p.row_tiles * p.ksplit);
   const int tb0 = zb * 4;
   const int rg0 = tile * 8 + wave * R;
   const int kb_begin = split * p.kb_per_split;
@@ -322,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     // 1 KiB contiguous per instruction; the last workgroup reads it back with the same thread mapping
     const __amdgpu_buffer_rsrc_t prs = shared_rsrc(p.partial);
     auto punit = [&](int sp, int r, int tb) __attribute__((always_inline)) {
-      return (uint32_t)((((((sp * (int)gridDim.z + zb) * (int)gridDim.x + tile) * 4 + wave) * R + r) * MTK + tb) * 64 + lane) * 16u;
+      return (uint32_t)((((((sp * p.zbs + zb) * p.row_tiles + tile) * 4 + wave) * R + r) * MTK + tb) * 64 + lane) * 16u;
     };
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -331,12 +340,12 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
-      int old = __hip_atomic_fetch_add(&p.counters[zb * gridDim.x + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int old = __hip_atomic_fetch_add(&p.counters[zb * p.row_tiles + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (old == p.ksplit - 1);
     }
     __syncthreads();
     if (!*s_last) return;
-    if (tid == 0) __hip_atomic_store(&p.counters[zb * gridDim.x + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(&p.counters[zb * p.row_tiles + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     request_epilogue_inputs();
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -884,7 +893,9 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.MT = MT;
   p.partial = m->partial;
   p.counters = m->counters;
-  dim3 grid(row_tiles, p.ksplit, zb), block(256);
+  p.row_tiles = row_tiles;
+  p.zbs = zb;
+  dim3 grid(row_tiles * p.ksplit * zb), block(256);
 #define LAUNCH(MTK_, WS_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WS_, EPI>), grid, block, 0, st, p);
   if (m->wsplit) {
     if (mtk == 1) LAUNCH(1, true) else if (mtk == 2) LAUNCH(2, true) else LAUNCH(4, true)
