@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
 // fragment order (packed weights, packed activations), so a K step of 32 is a straight 32 KiB copy into
 // LDS (16 weight fragments + 16 activation fragments) and every LDS read is a conflict-free 16-byte read.
 enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
+#define PGEMM_LDS_BYTES (3 * 2048 * 16)
 
 struct PGemmP {
   const u32x4* W;  // packed weights
@@ -122,7 +123,8 @@ struct PGemmP {
 
 template <int EPI>
 __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
-  __shared__ u32x4 smem[2][2048];  // per stage: units 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
+  // three stage buffers of 2048 sixteen-byte units: 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
+  extern __shared__ u32x4 smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
 
@@ -159,17 +161,22 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     srcA[i] = p.W + (int64_t)min(rg_tile + f, p.NRG - 1) * 64 + lane;
     srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64 + lane;
   }
-  // Two register sets carry the global loads of the next two k blocks; two fragment sets carry the LDS reads of the
-  // two 16-column halves of a k block.  Schedule of k block s (stage buffer s & 1):
-  //   request k block s+2 from memory                                  -> register set s & 1
-  //   read the fragments of half 1 of block s from LDS                  -> fragment set 1
-  //   16 MFMAs of half 0 (fragment set 0), with the copy of block s+1 (register set (s+1) & 1) into the other stage buffer
+  // Three register sets carry the memory requests of k blocks s+2 .. s+4, three LDS stage buffers hold k blocks
+  // s .. s+2, and two fragment sets carry the LDS reads of the two 16-column halves of a k block.
+  // Schedule of k block s (r = s mod 3):
+  //   first half : 16 MFMAs of half 0 (fragment set 0), one behind the other:
+  //                  8 memory requests for k block s+4            -> register set (r+1) mod 3
+  //                  8 LDS reads, half 1 of block s                -> fragment set 1
+  //                  4 LDS writes, weights of block s+2            (register set (r+2) mod 3 -> buffer (r+2) mod 3)
   //   barrier that waits for LDS traffic only (the requests to memory stay in flight across it)
-  //   read the fragments of half 0 of block s+1                         -> fragment set 0
-  //   16 MFMAs of half 1 (fragment set 1)
-  // so every LDS read, LDS write and memory request is issued at least 16 MFMAs before its data is needed.
-  // Past the last k block the requests are redirected to the last block and their copies are never read.
-  u32x4 ga0[4], gb0[4], ga1[4], gb1[4];
+  //   second half: 16 MFMAs of half 1 (fragment set 1), with
+  //                  8 LDS reads, half 0 of block s+1              -> fragment set 0
+  //                  4 LDS writes, activations of block s+2
+  // Every LDS read is issued 16 MFMAs before its data is needed, every memory request two k blocks before it is
+  // copied, and LDS reads + writes are the same 12 instructions in both halves (a two-buffer scheme must put all
+  // 8 writes into the first half, which then needs the whole LDS bandwidth).  Block s+2 is only read after the
+  // next barrier.  Past the last k block the requests are redirected to the last block; their copies are never read.
+  u32x4 ga0[4], gb0[4], ga1[4], gb1[4], ga2[4], gb2[4];
   u32x4 fa0[4], fb0[4], fa1[4], fb1[4];
   const int fm = lane & 31, fh = lane >> 5;
   auto request = [&](u32x4(&ga)[4], u32x4(&gb)[4], int kb) __attribute__((always_inline)) {
@@ -180,24 +187,25 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
       gb[i] = srcB[i][(int64_t)kbc * 128];
     }
   };
-  auto copy_in = [&](u32x4(&ga)[4], u32x4(&gb)[4], int buf) __attribute__((always_inline)) {
+  auto copy_a = [&](u32x4(&ga)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      smem[buf][(wave + 4 * i) * 64 + lane] = ga[i];
-      smem[buf][1024 + (wave + 4 * i) * 64 + lane] = gb[i];
-    }
+    for (int i = 0; i < 4; ++i) smem[buf * 2048 + (wave + 4 * i) * 64 + lane] = ga[i];
+  };
+  auto copy_b = [&](u32x4(&gb)[4], int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) smem[buf * 2048 + 1024 + (wave + 4 * i) * 64 + lane] = gb[i];
   };
   auto fetch = [&](u32x4(&fa)[4], u32x4(&fb)[4], int buf, int k16) __attribute__((always_inline)) {
-    const u32x4* A = smem[buf];
-    const u32x4* B = smem[buf] + 1024;
+    const u32x4* A = smem + buf * 2048;
+    const u32x4* B = smem + buf * 2048 + 1024;
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) fa[rb] = A[(wn * 8 + rb * 2 + (fm >> 4)) * 64 + ((k16 * 2 + fh) << 4) + (fm & 15)];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) fb[tb] = B[((wt * 4 + tb) * 2 + k16) * 64 + lane];
   };
-  auto mfma_rows = [&](u32x4(&fa)[4], u32x4(&fb)[4], int rb0, int rb1) __attribute__((always_inline)) {
+  auto mfma16 = [&](u32x4(&fa)[4], u32x4(&fb)[4]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int rb = rb0; rb < rb1; ++rb)
+    for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
       for (int tb = 0; tb < 4; ++tb)
         acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fa[rb]), as_f16x8(fb[tb]), acc[rb][tb], 0, 0, 0);
@@ -208,14 +216,13 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   };
   // sched_group_barrier masks: 0x008 MFMA, 0x020 memory read, 0x100 LDS read, 0x200 LDS write
-  auto k_block = [&](u32x4(&ga_new)[4], u32x4(&gb_new)[4], u32x4(&ga_next)[4], u32x4(&gb_next)[4], int s) __attribute__((always_inline)) {
-    const int buf = s & 1;
-    request(ga_new, gb_new, s + 2);
+  // r = s mod 3 selects the buffers; the register sets are passed in the matching rotation
+  auto k_block = [&](u32x4(&ga_req)[4], u32x4(&gb_req)[4], u32x4(&ga_cp)[4], u32x4(&gb_cp)[4], int s, int r) __attribute__((always_inline)) {
+    const int buf = r, buf1 = r == 2 ? 0 : r + 1, buf2 = r == 0 ? 2 : r - 1;
+    request(ga_req, gb_req, s + 4);
     fetch(fa1, fb1, buf, 1);
-    copy_in(ga_next, gb_next, buf ^ 1);
-    mfma_rows(fa0, fb0, 0, 4);
-    // issue order: one LDS read and one memory request behind each of the first 8 MFMAs, one LDS write behind
-    // each of the last 8, so the matrix pipe never waits for a block of other instructions to issue
+    copy_a(ga_cp, buf2);
+    mfma16(fa0, fb0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -225,36 +232,49 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      if (i < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     lds_barrier();
-    fetch(fa0, fb0, buf ^ 1, 0);
-    mfma_rows(fa1, fb1, 0, 4);
+    fetch(fa0, fb0, buf1, 0);
+    copy_b(gb_cp, buf2);
+    mfma16(fa1, fb1);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
 
   request(ga0, gb0, 0);
   request(ga1, gb1, 1);
-  copy_in(ga0, gb0, 0);
+  request(ga2, gb2, 2);
+  copy_a(ga0, 0);
+  copy_b(gb0, 0);
+  copy_a(ga1, 1);
+  copy_b(gb1, 1);
+  request(ga0, gb0, 3);
   lds_barrier();
   fetch(fa0, fb0, 0, 0);
   {
+    // k block s requests block s+4 into set (s+1) mod 3 and copies block s+2 out of set (s+2) mod 3
     int s = 0;
-    for (; s + 1 < p.KB; s += 2) {
-      k_block(ga0, gb0, ga1, gb1, s);      // even block: new requests into set 0, set 1 (block s+1) goes to LDS
-      k_block(ga1, gb1, ga0, gb0, s + 1);  // odd block: the other way round
+    for (; s + 2 < p.KB; s += 3) {
+      k_block(ga1, gb1, ga2, gb2, s, 0);
+      k_block(ga2, gb2, ga0, gb0, s + 1, 1);
+      k_block(ga0, gb0, ga1, gb1, s + 2, 2);
     }
-    if (s < p.KB) k_block(ga0, gb0, ga1, gb1, s);
+    if (s < p.KB) k_block(ga1, gb1, ga2, gb2, s, 0);
+    if (s + 1 < p.KB) k_block(ga2, gb2, ga0, gb0, s + 1, 1);
   }
   __syncthreads();  // the staging buffers are dead from here on; the residual epilogue reuses them
-  float(*red_ssq)[256] = reinterpret_cast<float(*)[256]>(&smem[0][0]);
+  float(*red_ssq)[256] = reinterpret_cast<float(*)[256]>(smem);
   (void)red_ssq;
 
   // acc[rb][tb][i] = Y^T[row][token]: row = (rg_tile + wn*8 + rb*2)*16 + (i/4)*8 + (lane/32)*4 + i%4, token = t_tile + wt*128 + tb*32 + lane%32
@@ -514,7 +534,12 @@ template <int EPI>
 static void launch_pgemm(PGemmP& p, hipStream_t st) {
   p.n_tt = (p.T + 255) / 256;
   p.n_rt = (p.NRG + 15) / 16;
-  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), 0, st, p);
+  static bool lds_enabled = false;  // per instantiation: allow 96 KiB of dynamic LDS
+  if (!lds_enabled) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, PGEMM_LDS_BYTES);
+    lds_enabled = true;
+  }
+  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), PGEMM_LDS_BYTES, st, p);
 }
 
 template <int HD>
