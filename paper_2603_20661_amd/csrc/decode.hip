@@ -11,10 +11,10 @@
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 // Cross-workgroup hand-over of partial results inside one kernel.  Partial tiles are written and read with
-// device-scope relaxed atomic accesses, which go through to memory shared by all XCDs instead of living in one
-// XCD's write-back L2; the producer waits for its stores to complete, the workgroup syncs, and one thread bumps a
-// device-scope counter.  This avoids device-scope fences, whose whole-L2 write-back / invalidate costs tens of
-// microseconds per kernel here.
+// device-scope (sc1) 16-byte accesses; the producer waits for its stores, the workgroup syncs, one thread issues a
+// device-scope release fence and bumps a device-scope counter; the workgroup that sees the last count reads the
+// tiles back.  Only that one thread per workgroup fences: a device-scope fence in every wavefront (write-back plus
+// invalidate of the whole L2) costs tens of microseconds per kernel here.
 // 16-byte accesses with device scope (cache-policy bit 4 = sc1 on gfx942/gfx950) through a raw buffer descriptor
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t shared_rsrc(const void* base) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
@@ -340,6 +340,10 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
+      // Device-scope release (L2 write-back) before the counter moves.  The barrier above orders every wavefront's
+      // completed stores before it.  Without it a last workgroup on another XCD now and then read a few stale
+      // cache lines of a partial tile, although the stores are write-through and had been waited for.
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
       int old = __hip_atomic_fetch_add(&p.counters[zb * p.row_tiles + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (old == p.ksplit - 1);
     }

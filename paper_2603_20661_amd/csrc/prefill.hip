@@ -458,18 +458,13 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
       vf0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
       vf1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
     }
-    if (base + 32 > ctx) {  // slots past the end of the sequence may hold anything: keep them out of the MFMA
-      const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
-      const uint32_t a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
-      const uint32_t a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
-      const uint32_t b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
-      const uint32_t b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
-#pragma unroll
-      for (int f = 0; f < NVF; ++f) {
-        vf0[f].x &= a01; vf0[f].y &= a23;
-        vf1[f].x &= b01; vf1[f].y &= b23;
-      }
-    }
+    // slots past the end of the sequence may hold anything: keep them out of the MFMA.  The masks are all-ones except
+    // in the sequence's last pair and are applied without a branch while the operand is put together.
+    const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
+    const uint32_t a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
+    const uint32_t a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
+    const uint32_t b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
+    const uint32_t b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
 #pragma unroll
     for (int hh = 0; hh < GH; ++hh) {
       f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -504,7 +499,7 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
       m_run[hh] = m_new;
 #pragma unroll
       for (int f = 0; f < NVF; ++f) {
-        u32x4 a = {vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y};
+        const u32x4 a = {vf0[f].x & a01, vf0[f].y & a23, vf1[f].x & b01, vf1[f].y & b23};
         oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
         oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[hh][f], 0, 0, 0);
       }
