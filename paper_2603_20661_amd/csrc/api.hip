@@ -300,6 +300,14 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->attn_maxrec = p.attn_maxrec;
   m->attn_waves = decode_attn_resident_waves(s.hd, s.G);
   if (m->attn_waves > MAX_ATTN_WAVES) m->attn_waves = MAX_ATTN_WAVES;
+  {
+    // the split-K hand-over may skip its L2 write-back only if workgroup ids equal modulo 8 share an XCD: probe it
+    // (4096 workgroups, results in the attention plan buffer, which is rewritten by every decode step)
+    const char* force = getenv("WWW_HANDOVER_FENCE");
+    const int ok = decode_probe_placement(m->attn_start, 4096, st);
+    if (ok < 0) { set_error("placement probe failed: %s", hipGetErrorString(hipGetLastError())); return fail(WWW_E_HIP); }
+    m->handover_fence = (ok == 0) || (force && atoi(force) != 0);
+  }
   *out = m;
   return WWW_OK;
 }

@@ -131,6 +131,7 @@ struct www_model {
   uint16_t* ap;        // packed [maxT][Fp] SwiGLU output
   int *row_seq, *row_pos, *tile_seq, *tile_q0, *meta;  // ragged-batch bookkeeping
   int attn_waves;  // wavefronts of the decode attention grid (all resident at once)
+  int handover_fence;  // 1: split-K partial tiles get a device-scope release fence (placement rule not confirmed)
   int attn_maxrec; // most partial records per (sequence, kv head)
   GraphEntry* graphs;
   int n_graphs;
@@ -150,6 +151,7 @@ void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in f
 // host-side launchers (decode.hip / prefill.hip / pack.hip)
 void set_error(const char* fmt, ...);
 int decode_attn_resident_waves(int hd, int G);
+int decode_probe_placement(int32_t* scratch_dev, int n, hipStream_t st);
 int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int32_t* table, int batch, float* logits, int32_t* next,
                hipStream_t st);
 int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const int32_t* lens, const int32_t* table, int batch, int T,

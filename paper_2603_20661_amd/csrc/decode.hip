@@ -4,6 +4,8 @@
 // operands, so every GEMM's inner loop is loads and MFMAs only.
 #include <stdlib.h>
 
+#include <vector>
+
 #include "common.h"
 
 #define NEG_INF (-__builtin_inff())
@@ -81,7 +83,8 @@ struct GemmP {
   const u32x4* X;    // packed activations
   int MT, M;         // token groups in X, valid tokens
   int kb_per_split, ksplit;
-  int row_tiles, zbs;  // grid: row_tiles * ksplit * zbs workgroups
+  int row_tiles, zbs;  // grid: 8 * ceil(row_tiles / 8) * ksplit * zbs workgroups
+  int fence_handover;  // 1: workgroups of one row tile may sit behind different L2s
   float* partial;    // [ksplit][zbs][row_tiles] tiles of 128 rows x 64 tokens
   int* counters;     // [zbs][row_tiles]
   const float* ssq_in;  // [token][SSQ_TILES]; row scale = rsqrt(sum of the first n_ssq_in entries / dim + eps); null: no scale
@@ -120,15 +123,17 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   volatile int* s_last = reinterpret_cast<volatile int*>(&lds[1][0]);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // Work items are numbered split-major, item = (zb * ksplit + split) * row_tiles + tile.  Consecutive workgroup ids
-  // are dealt round-robin to the 8 XCDs, each with its own L2; handing every XCD a contiguous run of items means that
-  // the workgroups behind one L2 share one or two k ranges, so that L2 fetches only that slice of the activations.
-  int item = blockIdx.x;
-  {
-    const int n_items = gridDim.x;
-    if (n_items % 8 == 0) item = (item % 8) * (n_items / 8) + item / 8;
-  }
-  const int tile = item % p.row_tiles, split = (item / p.row_tiles) % p.ksplit, zb = item / (p.row_tiles * p.ksplit);
+  // Workgroup id -> work item.  Consecutive workgroup ids are dealt round-robin to the XCDs (8 here; any power of two
+  // up to 8 divides 8), so ids that are equal modulo 8 run behind the same L2.  All k splits of a row tile get such
+  // ids: id = c + 8 * ((zb * tiles_per_xcd + lt) * ksplit + split) for row tile c + 8 * lt.  Their partial tiles then
+  // meet in one L2 and the split-K hand-over needs no L2 write-back.  The host checks this placement rule with a probe
+  // kernel when a model is loaded and sets fence_handover when it does not hold.
+  const int tiles_per_xcd = (p.row_tiles + 7) / 8;
+  const int slot = blockIdx.x >> 3;
+  const int split = slot % p.ksplit;
+  const int lt = (slot / p.ksplit) % tiles_per_xcd, zb = slot / (p.ksplit * tiles_per_xcd);
+  const int tile = (blockIdx.x & 7) + 8 * lt;
+  if (tile >= p.row_tiles) return;  // grid padding when the row tiles are not a multiple of 8
   const int tb0 = zb * 4;
   const int rg0 = tile * 8 + wave * R;
   const int kb_begin = split * p.kb_per_split;
@@ -340,10 +345,11 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
-      // Device-scope release (L2 write-back) before the counter moves.  The barrier above orders every wavefront's
-      // completed stores before it.  Without it a last workgroup on another XCD now and then read a few stale
-      // cache lines of a partial tile, although the stores are write-through and had been waited for.
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      // Partial tiles that have to cross to another XCD need a device-scope release (L2 write-back) before the
+      // counter moves: without it a last workgroup behind another L2 now and then read a few stale cache lines of
+      // a partial tile, although the stores are write-through and had been waited for.  The barrier above orders
+      // every wavefront's completed stores before this thread's fence.
+      if (p.fence_handover) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
       int old = __hip_atomic_fetch_add(&p.counters[zb * p.row_tiles + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (old == p.ksplit - 1);
     }
@@ -899,7 +905,8 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.counters = m->counters;
   p.row_tiles = row_tiles;
   p.zbs = zb;
-  dim3 grid(row_tiles * p.ksplit * zb), block(256);
+  p.fence_handover = m->handover_fence;
+  dim3 grid(8 * ((row_tiles + 7) / 8) * p.ksplit * zb), block(256);
 #define LAUNCH(MTK_, WS_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WS_, EPI>), grid, block, 0, st, p);
   if (m->wsplit) {
     if (mtk == 1) LAUNCH(1, true) else if (mtk == 2) LAUNCH(2, true) else LAUNCH(4, true)
@@ -926,6 +933,24 @@ int decode_attn_resident_waves(int hd, int G) {
 #undef OCC
   if (e != hipSuccess || per_cu < 1) { (void)hipGetLastError(); per_cu = 1; }
   return per_cu * cus * 4;
+}
+
+// Placement probe: every workgroup records the id of the XCD it runs on.
+__global__ __launch_bounds__(256) void xcc_probe_kernel(int32_t* __restrict__ out) {
+  const int xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15;  // HW_REG_XCC_ID, bits 3:0
+  if (threadIdx.x == 0) out[blockIdx.x] = xcc;
+}
+
+// 1 if workgroups whose ids are equal modulo 8 were all placed on the same XCD in a probe launch of n workgroups
+// (scratch_dev: n ints of device memory), 0 if not, -1 on a HIP error.
+int decode_probe_placement(int32_t* scratch_dev, int n, hipStream_t st) {
+  std::vector<int32_t> h(n);
+  hipLaunchKernelGGL(xcc_probe_kernel, dim3(n), dim3(256), 0, st, scratch_dev);
+  if (hipMemcpyAsync(h.data(), scratch_dev, (size_t)n * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
+  if (hipStreamSynchronize(st) != hipSuccess) return -1;
+  for (int i = 8; i < n; ++i)
+    if (h[i] != h[i & 7]) return 0;
+  return 1;
 }
 
 int decode_MT(int batch) { return batch <= 16 ? 1 : batch <= 32 ? 2 : ((batch + 63) / 64) * 4; }

@@ -159,10 +159,14 @@ def test_full_width_layers_at_bench_batch(shape, batch):
     check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
 
 
-def test_repeated_calls_are_bitwise_identical():
+@pytest.mark.parametrize("fence", ["0", "1"])
+def test_repeated_calls_are_bitwise_identical(fence, monkeypatch):
     """GPU vs GPU: the same decode step and the same prefill, issued again and again on one model, give the same bits.
     Split-K partial tiles travel between workgroups on different XCDs inside one kernel; a hand-over without a
-    device-scope release showed up here as a few differing logits in a few per cent of the calls."""
+    device-scope release showed up here as a few differing logits in a few per cent of the calls.  Both hand-over modes
+    are run: the default (all splits of a row tile behind one L2, confirmed by a placement probe at load, no fence) and
+    the fallback with the fence (WWW_HANDOVER_FENCE=1, read when a model is loaded)."""
+    monkeypatch.setenv("WWW_HANDOVER_FENCE", fence)
     shape = WIDE1B
     batch = 32
     lens = (1 + synth.uniform_i32(batch, 11, batch, 40)).astype(np.int32)
