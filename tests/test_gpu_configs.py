@@ -1,0 +1,194 @@
+"""GPU parity on the two composite configurations, at their full widths, batch sizes and sequence lengths:
+
+  * the duel-and-judge round (Sec. 4.2 of the paper: two executors answer the same request, a judge reads both answers
+    in one pass): 32 prompts of 768 tokens decoded 256 tokens each by a 1B-wide and by an 8B-wide model that are
+    resident together, then an 8B-wide judge prefill over prompt + answer A + answer B (1280 tokens per sequence);
+  * the long-context mixed batch: 128 sequences with Zipf(1.2) lengths in [256, 16384], 512-token prefill chunks
+    interleaved with decode steps, block tables scattered over a KV pool that fills 90 % of the free device memory
+    (element offsets beyond 32 bits).
+
+Only the depth is cut (two layers), so that the CPU oracle can replay sampled sequences in seconds: sequences are
+independent, so the oracle runs the sampled ones alone, fed with the tokens the GPU generated.  Bars as everywhere:
+max |dlogit| <= 3e-2, greedy agreement >= 99 %, no non-finite logit anywhere (the pools start NaN-filled)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2603_20661_amd import synth
+from helpers import GpuSession
+
+pytestmark = pytest.mark.gpu
+
+TOL = 3e-2
+AGREE = 0.99
+
+WIDE8B = dataclasses.replace(synth.M8B, name="wide8b", n_layers=2, seed=31)
+WIDE1B = dataclasses.replace(synth.M1B, name="wide1b", n_layers=2, seed=32)
+
+
+def oracle_replay(shape, blob, prompt, generated):
+    """One sequence alone through the oracle: prefill of `prompt`, then one decode step per entry of `generated`
+    (teacher-forced).  Returns logits [1 + len(generated), V]: after the prompt and after each appended token."""
+    from oracle import oracle as O
+    n = len(prompt) + len(generated)
+    m = O.OracleModel(shape, blob, max_seqs=1, max_ctx=n + 1)
+    out = []
+    lg, _, _ = m.forward(prompt, [len(prompt)], [len(prompt)], seq_ids=[0])
+    out.append(lg[0])
+    for i, t in enumerate(generated):
+        lg, _, _ = m.forward([t], [1], [len(prompt) + i + 1], seq_ids=[0])
+        out.append(lg[0])
+    m.close()
+    return np.stack(out)
+
+
+def summarize(what, gpu_logits, gpu_next, ref_logits):
+    """gpu_logits / ref_logits [n, V]; gpu_next [n] = the GPU's greedy tokens for the same rows"""
+    assert np.isfinite(gpu_logits).all(), f"{what}: non-finite logits"
+    err = float(np.abs(gpu_logits - ref_logits).max())
+    agree = float((ref_logits.argmax(-1) == gpu_next).mean())
+    print(f"{what}: max|dlogit|={err:.3e} agreement={agree:.4f} samples={len(gpu_next)}", flush=True)
+    return err, agree
+
+
+def test_duel_and_judge_round_full_width():
+    n_seq, plen, steps = 32, 768, 256
+    lens = np.full(n_seq, plen, np.int32)
+    prompts = synth.tokens(12345, n_seq * plen, 32000).reshape(n_seq, plen)   # ids valid for both vocabularies
+    sample = [0, 21]
+    answers, sessions, blobs = {}, {}, {}
+    try:
+        for name, shape in (("A", WIDE1B), ("B", WIDE8B)):
+            blob = blobs[name] = synth.make_blob(shape, gain_std=0.05)
+            cap = lens + steps + 1
+            mbs = int((cap.max() + 15) // 16)
+            nb = int(((cap + 15) // 16).sum()) + 11
+            table = synth.block_tables(7 + len(name), cap, nb, mbs, permute=True)
+            # the 8B-wide model also serves as the judge: room for 32 more sequences of 1280 tokens
+            jcap = plen + 2 * steps
+            jmbs = (jcap + 15) // 16
+            if name == "B":
+                mbs = max(mbs, jmbs)
+                nb += n_seq * jmbs
+                table = synth.block_tables(9, np.concatenate([cap, np.full(n_seq, jcap)]), nb, mbs, permute=True)
+            sess = sessions[name] = GpuSession(shape, blob, n_seq, mbs * 16, n_seq * max(plen, jcap if name == "B" else 0), nb)
+            lg, nxt = sess.prefill(prompts.reshape(-1), lens, lens, table[:n_seq])
+            logits, toks = [lg[sample]], [nxt.copy()]
+            cur = lens.copy()
+            for _ in range(steps):
+                cur = cur + 1
+                lg, nxt = sess.decode(toks[-1], cur, table[:n_seq])
+                assert np.isfinite(lg).all()
+                logits.append(lg[sample])
+                toks.append(nxt.copy())
+            toks = np.stack(toks)                    # [steps + 1, n_seq]; the first `steps` rows are the answer
+            answers[name] = toks[:steps].T           # [n_seq, steps]
+            g = np.stack(logits)                     # [steps + 1, len(sample), V]
+            worst, hits, total = 0.0, 0, 0
+            for k, b in enumerate(sample):
+                ref = oracle_replay(shape, blob, prompts[b], toks[:steps, b])
+                err, agree = summarize(f"duel executor {name} ({shape.name}), sequence {b}", g[:, k], toks[:, b], ref)
+                worst = max(worst, err)
+                hits += agree * (steps + 1)
+                total += steps + 1
+            assert worst <= TOL and hits / total >= AGREE
+            if name == "B":
+                judge_table = table[n_seq:]
+        # judge pass: one prefill of prompt | answer A | answer B per sequence, logits at the last position
+        judge_in = np.concatenate([prompts, answers["A"], answers["B"]], axis=1).astype(np.int32)
+        jl = np.full(n_seq, judge_in.shape[1], np.int32)
+        lg, nxt = sessions["B"].prefill(judge_in.reshape(-1), jl, jl, judge_table)
+        assert np.isfinite(lg).all()
+        worst, hits = 0.0, 0
+        for b in sample:
+            ref = oracle_replay(WIDE8B, blobs["B"], judge_in[b], [])
+            err, agree = summarize(f"judge pass, sequence {b} ({judge_in.shape[1]} tokens)", lg[b:b + 1], nxt[b:b + 1], ref)
+            worst = max(worst, err)
+            hits += agree
+        assert worst <= TOL and hits == len(sample)
+    finally:
+        for s in sessions.values():
+            s.close()
+
+
+def test_long_context_mixed_batch_interleaved_schedule():
+    import torch
+    shape = WIDE8B
+    n_seq, chunk, budget, dec_steps = 128, 512, 8192, 64
+    lens = synth.lengths_zipf(2, n_seq, 1.2, 256, 16384).astype(np.int64)
+    cap = lens + dec_steps + 1
+    mbs = int((cap.max() + 15) // 16)
+    blob = synth.make_blob(shape, gain_std=0.05)
+    # KV pool over 90 % of the free device memory; the sequences' blocks are drawn from a permutation of all block ids
+    free_bytes, _ = torch.cuda.mem_get_info()
+    block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * shape.head_dim * 2
+    nb = int(0.90 * free_bytes) // block_bytes
+    table = synth.block_tables(2, cap, nb, mbs, permute=True)
+    used = table[table >= 0]
+    assert int(used.max()) * (16 * shape.n_kv_heads * shape.head_dim) > 2 ** 32, "the pool must reach past 32-bit element offsets"
+    prompts = [synth.tokens(1000 + b, int(lens[b]), shape.vocab) for b in range(n_seq)]
+    order = np.argsort(lens)
+    sample = [int(order[0]), int(order[n_seq // 2]), int(order[np.searchsorted(lens[order], 3000)])]
+    sess = GpuSession(shape, blob, n_seq, mbs * 16, budget, nb)
+    try:
+        done = np.zeros(n_seq, np.int64)           # prompt tokens already in the cache
+        ndec = np.zeros(n_seq, np.int64)           # decode steps taken
+        last_tok = np.zeros(n_seq, np.int32)
+        got = {b: {"logits": [], "next": []} for b in sample}
+        gen = {b: [] for b in sample}
+        rr = 0
+        n_prefill_calls = n_decode_calls = 0
+        while (ndec < dec_steps).any():
+            # one prefill call: chunks of up to 512 tokens, round-robin over the sequences still prefilling, 8192-token budget
+            pending = [b for b in list(range(rr, n_seq)) + list(range(rr)) if done[b] < lens[b]]
+            pick, left = [], budget
+            for b in pending:
+                q = int(min(chunk, lens[b] - done[b]))
+                if q > left:
+                    break
+                pick.append((b, q))
+                left -= q
+            if pick:
+                rr = (pick[-1][0] + 1) % n_seq
+                ids = np.array([b for b, _ in pick])
+                q = np.array([q for _, q in pick], np.int32)
+                packed = np.concatenate([prompts[b][done[b]: done[b] + qq] for b, qq in pick])
+                lg, nxt = sess.prefill(packed, q, (done[ids] + q).astype(np.int32), table[ids])
+                assert np.isfinite(lg).all()
+                n_prefill_calls += 1
+                done[ids] += q
+                for k, b in enumerate(ids):
+                    if done[b] == lens[b]:
+                        last_tok[b] = nxt[k]
+                        if b in got:
+                            got[b]["logits"].append(lg[k])
+                            got[b]["next"].append(nxt[k])
+            # one decode step over the sequences whose prompt is complete
+            ids = np.nonzero((done == lens) & (ndec < dec_steps))[0]
+            if len(ids):
+                cur = (lens[ids] + ndec[ids] + 1).astype(np.int32)
+                lg, nxt = sess.decode(last_tok[ids], cur, table[ids])
+                assert np.isfinite(lg).all()
+                n_decode_calls += 1
+                for k, b in enumerate(ids):
+                    if b in got:
+                        gen[b].append(int(last_tok[b]))
+                        got[b]["logits"].append(lg[k])
+                        got[b]["next"].append(nxt[k])
+                last_tok[ids] = nxt
+                ndec[ids] += 1
+        print(f"schedule: {n_prefill_calls} prefill calls, {n_decode_calls} decode steps, {int(lens.sum())} prompt tokens, "
+              f"longest {int(lens.max())}, pool {nb} blocks = {nb * block_bytes / 2**30:.0f} GiB", flush=True)
+        worst, hits, total = 0.0, 0, 0
+        for b in sample:
+            ref = oracle_replay(shape, blob, prompts[b], gen[b])
+            g = np.stack(got[b]["logits"])
+            assert len(g) == dec_steps + 1
+            err, agree = summarize(f"mixed batch, sequence {b} (prompt {int(lens[b])})", g, np.array(got[b]["next"]), ref)
+            worst = max(worst, err)
+            hits += agree * len(g)
+            total += len(g)
+        assert worst <= TOL and hits / total >= AGREE
+    finally:
+        sess.close()
