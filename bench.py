@@ -29,6 +29,38 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
+
+# HBM traffic of the dominant decode kernel class (decode_attn_kernel + decode_attn_merge_kernel), from two
+# `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE; profiles/decode_attention_8b_traffic.md).
+# Counter units per launch, averaged over the 256 launches of those runs; scale = bytes per unit / 1024, from what the
+# same counter read for the calibration copy above (131 087.4 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
+# of WRITE_SIZE for 262 144 KiB written); algorithmic bytes of those same launches for rescaling to another context.
+# Valid only for the kernel sources it was taken with: reported as null when their hash differs.
+TRAFFIC = {
+    "workload": "8b", "kernel": "decode_attention",
+    "fetch_units": 163131.7 + 1674.3, "write_units": 3112.7 + 1024.0,
+    "fetch_scale": 262144.0 / 131087.4, "write_scale": 1.0,
+    "algorithmic_bytes_of_measured_launches": 80383 * 4096,
+    "sources": ("paper_2603_20661_amd/csrc/decode.hip", "paper_2603_20661_amd/csrc/common.h"),
+    "sha256": "4520abaf866260606846ffc3f2dd40c186eca81ae1783fc3526ef4262f91fd94",
+}
+
+
+def measured_traffic(workload, kernel, algorithmic_bytes_per_launch):
+    """HBM bytes per launch of `kernel` from the stored counter readings, rescaled linearly to this launch's algorithmic
+    bytes (attention traffic is proportional to the context); None if there is no reading for this workload / kernel or the
+    kernel sources have changed since it was taken."""
+    import hashlib
+    if workload != TRAFFIC["workload"] or kernel != TRAFFIC["kernel"]:
+        return None
+    h = hashlib.sha256()
+    for f in TRAFFIC["sources"]:
+        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), f), "rb") as fh:
+            h.update(fh.read())
+    if h.hexdigest() != TRAFFIC["sha256"]:
+        return None
+    measured = (TRAFFIC["fetch_units"] * TRAFFIC["fetch_scale"] + TRAFFIC["write_units"] * TRAFFIC["write_scale"]) * 1024.0
+    return int(round(measured * algorithmic_bytes_per_launch / TRAFFIC["algorithmic_bytes_of_measured_launches"]))
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
 
 
@@ -192,7 +224,8 @@ def main():
     roofline = None
     if dom:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBS, 4),
+                    "traffic": measured_traffic(args.workload, dom, per_bytes[dom]),
                     "algorithmic_bytes_per_launch": int(per_bytes[dom]), "avg_launch_ms": kernels[dom]["avg_ms"]}
 
     cpu = None
