@@ -391,9 +391,11 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 // ------------------------------------------------------------------------------------------------
 // Causal paged flash attention for new tokens.  One workgroup = 64 consecutive new tokens of one
 // sequence x one kv head (x GH of its query heads); each wavefront owns 16 query positions and keeps
-// S^T = K Q^T / O^T = V^T P^T for its GH heads, so K/V fragments loaded once serve all of them.
+// S^T = K Q^T / O^T = V^T P^T for its GH heads.  The keys and values of a pair of blocks (32 keys) are
+// copied into LDS once per workgroup and read from there by the four wavefronts (the cache already stores them
+// in MFMA operand order, so the copy is verbatim); the next pair travels from memory while this one is used.
 template <int HD, int GH>
-__global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
                                                             const uint16_t* __restrict__ vplane, const int32_t* __restrict__ q_lens,
                                                             const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ table,
                                                             int mbs, int Hq, int Hkv, int G, const int32_t* __restrict__ tile_seq,
@@ -401,23 +403,28 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
                                                             const int32_t* __restrict__ cum_rows, float scale_log2,
                                                             uint16_t* __restrict__ op) {
   constexpr int NKF = HD / 32, NVF = HD / 16;
+  constexpr int CH = NKF * 64;         // 16-byte units of one block's keys (and of one block's values)
+  constexpr int NLD = 4 * CH / 256;    // units each thread moves per pair
+  __shared__ u32x4 kv[2][4 * CH];      // per pair: keys of block 0, keys of block 1, values of block 0, values of block 1
   const int tile = blockIdx.x;
   if (tile >= meta[0]) return;
   const int j = blockIdx.y;
   const int h0 = j * G + blockIdx.z * GH;  // first query head handled here
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = lane & 15, g = lane >> 4;
   const int b = tile_seq[tile];
   const int qlen = q_lens[b], ctx = seq_lens[b];
   const int prefix = ctx - qlen;
-  const int qw0 = tile_q0[tile] + wave * 16;  // first query (index among the new tokens) of this wavefront
-  if (qw0 >= qlen) return;
-  const int nq = min(16, qlen - qw0);
-  const int64_t row0 = (int64_t)cum_rows[b] + qw0;
+  const int tq0 = tile_q0[tile];
+  const int qw0 = tq0 + wave * 16;        // first query (index among the new tokens) of this wavefront
+  const bool active = qw0 < qlen;         // a wavefront past the end of the sequence only helps with the copies
+  const int nq = active ? min(16, qlen - qw0) : 1;
+  const int64_t row0 = (int64_t)cum_rows[b] + (active ? qw0 : 0);
   const int my_q = min(n, nq - 1);        // lanes past the end repeat the last query; their output is dropped
   const int qpos = prefix + qw0 + my_q;   // this lane's query position
-  const int kmax = prefix + qw0 + nq;     // keys 0 .. kmax-1 are visible to some query of the wavefront
+  const int kmax = active ? prefix + qw0 + nq : 0;  // keys 0 .. kmax-1 are visible to some query of the wavefront
   const int npairs = (kmax + 31) / 32;
+  const int npairs_wg = (prefix + min(qlen, tq0 + 64) + 31) / 32;  // pairs the workgroup walks through
   const int last_blk = (ctx - 1) / KV_BS;
   const int32_t* trow = table + (int64_t)b * mbs;
   const int QD = Hq * HD;
@@ -440,72 +447,135 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint16_t* __res
   }
 
   const int64_t blk_elems = (int64_t)KV_BS * HD;
-  for (int pr = 0; pr < npairs; ++pr) {
+  u32x4 stg[NLD];
+  // Block ids are fetched one pair ahead of the request that uses them, so the request never waits for the table.
+  // A pair past the workgroup's last one is redirected to the last one (in bounds, never used).
+  int id0 = 0, id1 = 0;
+  auto fetch_ids = [&](int pr) __attribute__((always_inline)) {
+    const int prc = min(pr, npairs_wg - 1);
+    id0 = trow[min(prc * 2, last_blk)];
+    id1 = trow[min(prc * 2 + 1, last_blk)];
+  };
+  auto request = [&]() __attribute__((always_inline)) {
+    const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
+    const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int u = tid + i * 256, c = u / CH, within = u % CH;
+      const uint16_t* src = (c < 2 ? kplane : vplane) + ((c & 1) ? off1 : off0) + within * 8;
+      stg[i] = *reinterpret_cast<const u32x4*>(src);
+    }
+  };
+  auto copy_in = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) kv[buf][tid + i * 256] = stg[i];
+  };
+  auto compute = [&](int buf, int pr) __attribute__((always_inline)) {
     const int base = pr * 32;
-    const int bi0 = base / KV_BS;
-    const int bi1 = min(bi0 + 1, last_blk);
-    const int64_t off0 = ((int64_t)trow[bi0] * Hkv + j) * blk_elems;
-    const int64_t off1 = ((int64_t)trow[bi1] * Hkv + j) * blk_elems;
     u32x4 kf0[NKF], kf1[NKF];
     u32x2 vf0[NVF], vf1[NVF];
+    const u32x2* v0p = reinterpret_cast<const u32x2*>(&kv[buf][2 * CH]);
+    const u32x2* v1p = reinterpret_cast<const u32x2*>(&kv[buf][3 * CH]);
 #pragma unroll
     for (int f = 0; f < NKF; ++f) {
-      kf0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
-      kf1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
+      kf0[f] = kv[buf][f * 64 + lane];
+      kf1[f] = kv[buf][CH + f * 64 + lane];
     }
-#pragma unroll
-    for (int f = 0; f < NVF; ++f) {
-      vf0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
-      vf1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
-    }
-    // slots past the end of the sequence may hold anything: keep them out of the MFMA.  The masks are all-ones except
-    // in the sequence's last pair and are applied without a branch while the operand is put together.
+    // slots past the end of the sequence may hold anything: keep them out of the MFMA (masks are all-ones elsewhere)
     const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
     const uint32_t a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
     const uint32_t a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
     const uint32_t b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
     const uint32_t b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
 #pragma unroll
-    for (int hh = 0; hh < GH; ++hh) {
-      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    for (int f = 0; f < NVF; ++f) {
+      vf0[f] = v0p[f * 64 + lane];
+      vf1[f] = v1p[f * 64 + lane];
+    }
+    // three passes over the GH heads (scores, softmax, values) rather than one head after the other: the heads are
+    // independent, so each pass is a run of independent MFMAs or of independent cross-lane exchanges
+    f32x4 s0[GH], s1[GH];
 #pragma unroll
-      for (int f = 0; f < NKF; ++f) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qf[hh][f], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qf[hh][f], s1, 0, 0, 0);
+    for (int hh = 0; hh < GH; ++hh) {
+      s0[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+      s1[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int f = 0; f < NKF; ++f)
+#pragma unroll
+      for (int hh = 0; hh < GH; ++hh) {
+        s0[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qf[hh][f], s0[hh], 0, 0, 0);
+        s1[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qf[hh][f], s1[hh], 0, 0, 0);
       }
-      float sc[8];
-      float mx = NEG_INF;
+    float sc[GH][8], mx[GH];
+#pragma unroll
+    for (int hh = 0; hh < GH; ++hh) {
+      mx[hh] = NEG_INF;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        sc[i] = (base + 4 * g + i <= qpos) ? s0[i] * scale_log2 : NEG_INF;
-        sc[4 + i] = (base + 16 + 4 * g + i <= qpos) ? s1[i] * scale_log2 : NEG_INF;
-        mx = fmaxf(mx, fmaxf(sc[i], sc[4 + i]));
+        sc[hh][i] = (base + 4 * g + i <= qpos) ? s0[hh][i] * scale_log2 : NEG_INF;
+        sc[hh][4 + i] = (base + 16 + 4 * g + i <= qpos) ? s1[hh][i] * scale_log2 : NEG_INF;
+        mx[hh] = fmaxf(mx[hh], fmaxf(sc[hh][i], sc[hh][4 + i]));
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[hh], mx);
-      // a query whose visible keys all lie in later pairs has m_new = -inf here: keep its state untouched
-      const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - m_use);
+    }
+#pragma unroll
+    for (int hh = 0; hh < GH; ++hh) mx[hh] = fmaxf(mx[hh], __shfl_xor(mx[hh], 16));
+#pragma unroll
+    for (int hh = 0; hh < GH; ++hh) mx[hh] = fmaxf(mx[hh], __shfl_xor(mx[hh], 32));
+    f16x8 pbv[GH];
+#pragma unroll
+    for (int hh = 0; hh < GH; ++hh) {
+      // m_run is a reference point for the exponentials, not necessarily the running maximum: the result o / l does
+      // not depend on it.  It is moved (and o, l rescaled) only when a score exceeds it by more than 2^8, so that
+      // probabilities stay below 256 in fp16; after the first pairs of a sequence that is rare, and the 4 * NVF
+      // accumulator registers per head are then left alone.
+      if (__any(mx[hh] > m_run[hh] + 8.f)) {
+        const float m_new = fmaxf(m_run[hh], mx[hh]);
+        // a query whose visible keys all lie in later pairs has m_new = -inf here: keep its state untouched
+        const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - ((m_new == NEG_INF) ? 0.f : m_new));
+        l_run[hh] *= alpha;
+        m_run[hh] = m_new;
+#pragma unroll
+        for (int f = 0; f < NVF; ++f) {
+          oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
+        }
+      }
+      const float m_use = (m_run[hh] == NEG_INF) ? 0.f : m_run[hh];
       union { uint16_t s[8]; f16x8 v; } pb;
       float psum = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        float pv = __builtin_amdgcn_exp2f(sc[i] - m_use);
+        float pv = __builtin_amdgcn_exp2f(sc[hh][i] - m_use);
         psum += pv;
         pb.s[i] = f32_to_f16_sat(pv);
       }
-      l_run[hh] = l_run[hh] * alpha + psum;
-      m_run[hh] = m_new;
-#pragma unroll
-      for (int f = 0; f < NVF; ++f) {
-        const u32x4 a = {vf0[f].x & a01, vf0[f].y & a23, vf1[f].x & b01, vf1[f].y & b23};
-        oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
-        oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[hh][f], 0, 0, 0);
-      }
+      l_run[hh] += psum;
+      pbv[hh] = pb.v;
     }
+#pragma unroll
+    for (int f = 0; f < NVF; ++f) {
+      const u32x4 a = {vf0[f].x & a01, vf0[f].y & a23, vf1[f].x & b01, vf1[f].y & b23};
+#pragma unroll
+      for (int hh = 0; hh < GH; ++hh)
+        oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pbv[hh], oacc[hh][f], 0, 0, 0);
+    }
+  };
+
+  fetch_ids(0);
+  request();
+  fetch_ids(1);
+  copy_in(0);
+  __syncthreads();
+  for (int pr = 0; pr < npairs_wg; ++pr) {
+    request();          // pair pr + 1
+    fetch_ids(pr + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    if (pr < npairs) compute(pr & 1, pr);
+    __builtin_amdgcn_sched_barrier(0);
+    copy_in((pr + 1) & 1);
+    __syncthreads();
   }
-  if (n >= nq) return;
+  if (!active || n >= nq) return;
 #pragma unroll
   for (int hh = 0; hh < GH; ++hh) {
     float l = l_run[hh];
@@ -541,7 +611,9 @@ template <int HD>
 static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* vplane, const int32_t* qlens, const int32_t* lens,
                          const int32_t* table, int max_tiles, hipStream_t st) {
   const int G = m->G;
-  const int GH = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  // two query heads per workgroup pass: their accumulators and operands fit 256 registers, so two workgroups share a
+  // compute unit and one hides the other's softmax and LDS latencies (four heads per pass at one workgroup per unit: 1.5x slower)
+  const int GH = (G % 2 == 0) ? 2 : 1;
   dim3 grid(max_tiles, m->Hkv, G / GH), block(256);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const int32_t* cum_rows = m->meta + 16;
