@@ -56,6 +56,9 @@ extern "C" {
 #define WWW_E_ABI_MISMATCH (-3) /* config.abi_version != WWW_ABI_VERSION */
 #define WWW_E_CAPACITY (-4)     /* batch > max_batch, tokens > max_prefill_tokens, ... */
 #define WWW_E_HIP (-5)          /* a HIP runtime call failed; message holds hipGetErrorString */
+#define WWW_E_STALE (-6)        /* a kernel of an earlier call on this model found the workgroup placement rule of its
+                                   split-K hand-over violated: results since the last successful call are unreliable; the
+                                   model has switched to the fenced hand-over, repeat those calls (never seen so far) */
 
 #define WWW_DTYPE_F32 0u  /* weights given in fp32: kept as two fp16 terms (hi + lo) */
 #define WWW_DTYPE_BF16 1u /* weights given in bf16: converted to fp16 (exact for |w| >= 2^-17) */
@@ -98,7 +101,7 @@ int www_model_load(const www_config* cfg, const void* weights_dev, void* kv_pool
  *   block_table_dev  int32 [batch][max_blocks_per_seq]; unused entries are ignored
  *   logits_dev       fp32 [batch][vocab], logits at the LAST new position of each sequence; may be NULL
  *   next_tokens_dev  int32 [batch], argmax of those logits; may be NULL
- * batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY (batch > max_batch, total_q_tokens > max_prefill_tokens), HIP. */
+ * batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY (batch > max_batch, total_q_tokens > max_prefill_tokens), HIP, STALE. */
 int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_dev, const int32_t* seq_lens_dev,
                 const int32_t* block_table_dev, int32_t batch, int32_t total_q_tokens, float* logits_dev, int32_t* next_tokens_dev,
                 void* hip_stream);
@@ -110,7 +113,7 @@ int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_d
  *   next_tokens_dev  int32 [batch] greedy next token; may be NULL
  * The step is replayed from a captured HIP graph keyed on (batch, pointers, stream); lengths, tables
  * and tokens are read from device memory at run time, so the same arrays can be updated in place
- * between steps.  batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY, HIP. */
+ * between steps.  batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY, HIP, STALE. */
 int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
                     int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream);
 

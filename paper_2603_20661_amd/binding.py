@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwww.so")
 
 ABI_VERSION = 1
-E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP = -1, -2, -3, -4, -5
+E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP, E_STALE = -1, -2, -3, -4, -5, -6
 EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_model_free", "www_last_error",
            "www_debug_slots", "www_debug_read", "www_debug_profile", "www_debug_profile_read")
 

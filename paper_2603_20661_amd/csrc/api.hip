@@ -80,6 +80,20 @@ static int check_config(const www_config* c) {
   return WWW_OK;
 }
 
+// The unfenced split-K hand-over relies on a placement rule that is probed at load and re-checked by the kernels.  If
+// a kernel has reported a violation, results since the last check are unreliable: switch the model to the fenced
+// hand-over (cached graphs hold the old kernel arguments and are dropped) and tell the caller.
+static int check_placement_fault(www_model* m) {
+  if (!m->fault_host || !*m->fault_host) return WWW_OK;
+  *m->fault_host = 0;
+  m->handover_fence = 1;
+  for (int i = 0; i < m->n_graphs; ++i) (void)hipGraphExecDestroy(m->graphs[i].exec);
+  m->n_graphs = 0;
+  set_error("split-K partners ran on different XCDs: results of the calls since the last successful one are unreliable; "
+            "the model now uses the fenced hand-over, repeat those calls");
+  return WWW_E_STALE;
+}
+
 static uint64_t align256(uint64_t n) { return (n + 255) / 256 * 256; }
 
 // byte offsets of everything inside the workspace
@@ -133,7 +147,7 @@ static void make_plan(const www_config* c, Plan& p) {
   }
   p.zero_begin = off;
   const uint64_t Mpad = (uint64_t)s.MTmax * 16;
-  p.counters = take((65536 + (uint64_t)s.maxB * s.Hkv) * 4);
+  p.counters = take((uint64_t)65536 * 8);
   p.h = take(Mpad * s.d * 4);
   p.ssq = take((uint64_t)SSQ_TILES * s.maxB * 4);
   p.q = take(Mpad * s.QD * 4);
@@ -290,7 +304,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->kv_plane = (int64_t)cfg->num_kv_blocks * s.Hkv * KV_BS * s.hd;
   m->h = (float*)(ws + p.h); m->ssq = (float*)(ws + p.ssq); m->q_hi = (uint16_t*)(ws + p.q); m->q_lo = m->q_hi + (size_t)s.MTmax * 16 * s.QD;
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
-  m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (int*)(ws + p.counters);
+  m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (unsigned long long*)(ws + p.counters);
   m->logits_buf = (float*)(ws + p.logits); m->last_tok = (int*)(ws + p.last_tok);
   m->attn_hdr = (int*)(ws + p.attn_hdr); m->attn_start = (int*)(ws + p.attn_start); m->attn_pref = (int*)(ws + p.attn_pref);
   m->argmax_val = (float*)(ws + p.argmax_val); m->argmax_idx = (int*)(ws + p.argmax_idx);
@@ -307,6 +321,14 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
     const int ok = decode_probe_placement(m->attn_start, 4096, st);
     if (ok < 0) { set_error("placement probe failed: %s", hipGetErrorString(hipGetLastError())); return fail(WWW_E_HIP); }
     m->handover_fence = (ok == 0) || (force && atoi(force) != 0);
+    // a pinned host word the kernels set if, against the probe, the splits of a row tile ever run on different XCDs
+    if (hipHostMalloc((void**)&m->fault_host, sizeof(int), hipHostMallocMapped) != hipSuccess ||
+        hipHostGetDevicePointer((void**)&m->fault_dev, m->fault_host, 0) != hipSuccess) {
+      set_error("pinned flag allocation failed: %s", hipGetErrorString(hipGetLastError()));
+      if (m->fault_host) (void)hipHostFree(m->fault_host);
+      return fail(WWW_E_HIP);
+    }
+    *m->fault_host = 0;
   }
   *out = m;
   return WWW_OK;
@@ -317,6 +339,7 @@ WWW_EXPORT int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_
                            int32_t* next_tokens_dev, void* hip_stream) {
   if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
   if (batch < 0 || total_q_tokens < 0 || total_q_tokens < batch) { set_error("bad batch / total_q_tokens"); return WWW_E_INVALID_ARG; }
+  if (int rcp = check_placement_fault(m)) return rcp;
   if (batch == 0) return WWW_OK;  // nothing to do; the pointers of empty arrays may be NULL
   if (!tokens_dev || !q_lens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
@@ -332,6 +355,7 @@ WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, con
                                int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream) {
   if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
   if (batch < 0) { set_error("negative batch"); return WWW_E_INVALID_ARG; }
+  if (int rcp = check_placement_fault(m)) return rcp;
   if (batch == 0) return WWW_OK;  // nothing to do; the pointers of empty arrays may be NULL
   if (!last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
@@ -373,6 +397,7 @@ WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, con
 WWW_EXPORT void www_model_free(www_model* m) {
   if (!m) return;
   for (int i = 0; i < m->n_graphs; ++i) (void)hipGraphExecDestroy(m->graphs[i].exec);
+  if (m->fault_host) (void)hipHostFree(m->fault_host);
   if (m->prof) {
     for (hipEvent_t e : m->prof->ev) (void)hipEventDestroy(e);
     delete m->prof;

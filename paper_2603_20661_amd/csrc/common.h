@@ -119,7 +119,9 @@ struct www_model {
   int *attn_hdr, *attn_start, *attn_pref;  // per-step plan of the decode attention: totals, per-wavefront start, prefix of pair counts
   float* argmax_val;  // [maxB][32] per-slice maxima of the logits and
   int* argmax_idx;    // their indices
-  int* counters;
+  unsigned long long* counters;  // split-K arrival counters
+  int* fault_host;  // pinned host word the kernels set when the placement rule of the split-K hand-over is violated,
+  int* fault_dev;   // and its device address
   float* logits_buf;  // used when the caller passes no logits buffer
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
   // prefill-path buffers

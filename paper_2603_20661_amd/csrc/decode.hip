@@ -86,7 +86,8 @@ struct GemmP {
   int row_tiles, zbs;  // grid: 8 * ceil(row_tiles / 8) * ksplit * zbs workgroups
   int fence_handover;  // 1: workgroups of one row tile may sit behind different L2s
   float* partial;    // [ksplit][zbs][row_tiles] tiles of 128 rows x 64 tokens
-  int* counters;     // [zbs][row_tiles]
+  unsigned long long* counters;  // [zbs][row_tiles]: arrivals in bits 0-7, arrivals per XCD in eight 5-bit fields above
+  int* fault_flag;   // host-visible; set when the splits of a row tile turn out to sit on different XCDs
   const float* ssq_in;  // [token][SSQ_TILES]; row scale = rsqrt(sum of the first n_ssq_in entries / dim + eps); null: no scale
   int n_ssq_in;
   float inv_dim, eps;
@@ -350,12 +351,21 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
       // a partial tile, although the stores are write-through and had been waited for.  The barrier above orders
       // every wavefront's completed stores before this thread's fence.
       if (p.fence_handover) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-      int old = __hip_atomic_fetch_add(&p.counters[zb * p.row_tiles + tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *s_last = (old == p.ksplit - 1);
+      // the counter also records on which XCD each split ran, so that the last workgroup can tell whether the
+      // placement rule held for this tile (the unfenced hand-over is only sound if it did)
+      const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;  // HW_REG_XCC_ID
+      const unsigned long long mine = 1ull + (xcc < 8 ? 1ull << (8 + 5 * xcc) : 0ull);
+      const unsigned long long old = __hip_atomic_fetch_add(&p.counters[zb * p.row_tiles + tile], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const bool last = (int)(old & 0xff) == p.ksplit - 1;
+      *s_last = last;
+      if (last && !p.fence_handover) {
+        const unsigned same = xcc < 8 ? (unsigned)(((old + mine) >> (8 + 5 * xcc)) & 31u) : 0u;
+        if ((int)same != p.ksplit) *p.fault_flag = 1;
+      }
     }
     __syncthreads();
     if (!*s_last) return;
-    if (tid == 0) __hip_atomic_store(&p.counters[zb * p.row_tiles + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(&p.counters[zb * p.row_tiles + tile], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     request_epilogue_inputs();
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -903,6 +913,7 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.MT = MT;
   p.partial = m->partial;
   p.counters = m->counters;
+  p.fault_flag = m->fault_dev;
   p.row_tiles = row_tiles;
   p.zbs = zb;
   p.fence_handover = m->handover_fence;
