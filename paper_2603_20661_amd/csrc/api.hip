@@ -179,7 +179,7 @@ static void make_plan(const www_config* c, Plan& p) {
   p.argmax_idx = take((uint64_t)s.maxB * 32 * 4);
   p.hp = take((uint64_t)s.maxT * s.d * 4);
   const uint64_t Tpad = ((uint64_t)s.maxT + 255) / 256 * 256;  // packed activation buffers hold whole 256-token tiles
-  p.ssq_p = take(Tpad * ((uint64_t)s.d / 256 + 1) * 4);
+  p.ssq_p = take(Tpad * (uint64_t)PSSQ * 4);
   p.xn = take(Tpad * s.d * 2);
   p.qp = take((uint64_t)s.maxT * s.QD * 2);
   p.op = take(Tpad * s.QD * 2);

@@ -142,6 +142,7 @@ struct www_model {
 };
 
 #define MAX_ATTN_WAVES 8192  // upper bound of the decode attention grid, in wavefronts (sizes its plan buffer)
+#define PSSQ 32            // entries per token of the prefill path's sum-of-squares table (d_model / 256 row tiles at most)
 #define SSQ_TILES 64       // most row tiles of a residual-producing GEMM (d_model / 128)
 #define GEMM_TILE_ROWS 128 // rows of W per workgroup of the skinny GEMM
 #define MAX_KSPLIT 16

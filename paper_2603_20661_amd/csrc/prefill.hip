@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
     if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
-  if (threadIdx.x == 0) ssq[r] = red[0];
+  if (threadIdx.x == 0) ssq[(int64_t)r * PSSQ] = red[0];  // row r of the [token][PSSQ] table, one entry in use
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -108,7 +108,6 @@ struct PGemmP {
   // RMSNorm scale of the input rows (QKV and SwiGLU GEMMs): rsqrt(sum_i ssq_in[i][t] / dim + eps) multiplies the result
   const float* ssq_in;
   int n_ssq_in;
-  int64_t ssq_stride;
   float inv_dim, eps;
   // residual epilogue: h += result; also emits the next GEMM's operand fp16(h * gain_next) and partial sums of squares
   float* hp;
@@ -279,45 +278,101 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 
   // acc[rb][tb][i] = Y^T[row][token]: row = (rg_tile + wn*8 + rb*2)*16 + (i/4)*8 + (lane/32)*4 + i%4, token = t_tile + wt*128 + tb*32 + lane%32
   const int hsel = lane >> 5;
+  // Everything the epilogue needs from memory per token is requested up front for all four token groups (one memory
+  // round trip, two for the KV block ids), and the per-element operands of a token group (residual rows, rotary
+  // factors) in one batch per group: a wavefront has no partner on its SIMD to hide a chain of dependent loads behind.
+  // Addresses of tokens past the end are clamped; their results are dropped.
+  int tcl[4];
+  bool tok_ok[4];
+  float scale[4];
+  int pos[4], blk[4];
 #pragma unroll
   for (int tb = 0; tb < 4; ++tb) {
     const int t = t_tile + wt * 128 + tb * 32 + (lane & 31);
-    if (t >= p.T) continue;  // its red_ssq slot stays unwritten and is never read: the final store is masked the same way
-    int pos = 0;
-    int64_t kvbase = 0;
-    int tok = 0;
+    tok_ok[tb] = t < p.T;
+    tcl[tb] = min(t, p.T - 1);
+    scale[tb] = 1.f;
+    pos[tb] = 0;
+    blk[tb] = 0;
+  }
+  if constexpr (EPI != PEPI_RESID) {
     if constexpr (EPI == PEPI_QKV) {
-      pos = p.row_pos[t];
-      int64_t slot = kv_slot(p.table + (int64_t)p.row_seq[t] * p.mbs, pos);
-      kvbase = (slot / KV_BS) * p.Hkv;
-      tok = (int)(slot % KV_BS);
-    }
-    float scale = 1.f;
-    if constexpr (EPI != PEPI_RESID) {
-      float ss = 0.f;
-      for (int i0 = 0; i0 < p.n_ssq_in; i0 += 8) {  // tile order, eight loads in flight
-        float sv[8];
+      int seq[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sv[u] = p.ssq_in[(int64_t)min(i0 + u, p.n_ssq_in - 1) * p.ssq_stride + t];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-          if (i0 + u < p.n_ssq_in) ss += sv[u];
+      for (int tb = 0; tb < 4; ++tb) {
+        pos[tb] = p.row_pos[tcl[tb]];
+        seq[tb] = p.row_seq[tcl[tb]];
       }
-      scale = rsqrtf(ss * p.inv_dim + p.eps);
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) blk[tb] = kv_block_id(p.table + (int64_t)seq[tb] * p.mbs, pos[tb]);
+    }
+    // the tokens' rows of the sum-of-squares table, [token][PSSQ], two token groups at a time (64 registers);
+    // entries past n_ssq_in are masked, the rest is added in tile order
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      if (!p.ssq_in) break;  // no normalisation requested: the scales stay 1
+      f32x4 sq[2][PSSQ / 4];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int c = 0; c < PSSQ / 4; ++c)
+          sq[u][c] = *reinterpret_cast<const f32x4*>(p.ssq_in + (int64_t)tcl[half * 2 + u] * PSSQ + c * 4);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float ss = 0.f;
+#pragma unroll
+        for (int c = 0; c < PSSQ / 4; ++c)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ss += (c * 4 + e < p.n_ssq_in) ? sq[u][c][e] : 0.f;
+        scale[half * 2 + u] = rsqrtf(ss * p.inv_dim + p.eps);
+      }
+    }
+  }
+  f32x4 gv[4][4];  // next norm's gain for this lane's 16 x 4 rows (residual epilogue)
+  if constexpr (EPI == PEPI_RESID) {
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
+        gv[rb][q4] = *reinterpret_cast<const f32x4*>(p.gain_next + rg * 16 + (q4 & 1) * 8 + hsel * 4);
+      }
+  }
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) {
+    __builtin_amdgcn_sched_barrier(0);  // one token group at a time: keeps the accumulator copies of the others out of the way
+    const int t = tcl[tb];
+    const bool ok = tok_ok[tb];
+    const int64_t slot = kv_slot_in_block(blk[tb], pos[tb]);
+    const int64_t kvbase = (slot / KV_BS) * p.Hkv;
+    const int tok = (int)(slot % KV_BS);
+    // one batch of loads for this token group: residual rows (RESID) or rotary factors (QKV)
+    f32x4 pre[4][4];
+    if constexpr (EPI != PEPI_SWIGLU) {
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
+          const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
+          if constexpr (EPI == PEPI_RESID) pre[rb][q4] = *reinterpret_cast<const f32x4*>(p.hp + (int64_t)t * p.d + n0);
+          else pre[rb][q4] = *reinterpret_cast<const f32x4*>(p.rope + (int64_t)pos[tb] * (p.hd / 2) + ((n0 % p.hd) >> 1));
+        }
     }
     float ssq_tok = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
       const int rgb = rg_tile + wn * 8 + rb * 2;  // first of the two row groups of this 32-row block
       if constexpr (EPI == PEPI_SWIGLU) {
-        if (rgb + 1 >= p.NRG) continue;
+        if (!ok || rgb + 1 >= p.NRG) continue;
 #pragma unroll
         for (int q4 = 0; q4 < 2; ++q4) {
           int f0 = (rgb >> 1) * 16 + q4 * 8 + hsel * 4;
           union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            float g = acc[rb][tb][q4 * 4 + i] * scale, u = acc[rb][tb][(q4 + 2) * 4 + i] * scale;
+            float g = acc[rb][tb][q4 * 4 + i] * scale[tb], u = acc[rb][tb][(q4 + 2) * 4 + i] * scale[tb];
             o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
           }
           *reinterpret_cast<u32x2*>(p.ap + packed_p_offset(t, f0, p.Fp >> 4)) = o.v;
@@ -326,35 +381,32 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int rg = rgb + (q4 >> 1);
-          if (rg >= p.NRG) continue;
+          if (!ok || rg >= p.NRG) continue;
           const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
           float v4[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i] * scale;
+          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i] * scale[tb];
           if constexpr (EPI == PEPI_RESID) {
-            float4* dst = reinterpret_cast<float4*>(p.hp + (int64_t)t * p.d + n0);
-            float4 hv = *dst;
-            const float hn[4] = {hv.x + v4[0], hv.y + v4[1], hv.z + v4[2], hv.w + v4[3]};
-            *dst = make_float4(hn[0], hn[1], hn[2], hn[3]);
-            const float4 gv = *reinterpret_cast<const float4*>(p.gain_next + n0);
-            const float gn[4] = {gv.x, gv.y, gv.z, gv.w};
+            const f32x4 hv = pre[rb][q4], g4 = gv[rb][q4];
+            const float hn[4] = {hv[0] + v4[0], hv[1] + v4[1], hv[2] + v4[2], hv[3] + v4[3]};
+            *reinterpret_cast<float4*>(p.hp + (int64_t)t * p.d + n0) = make_float4(hn[0], hn[1], hn[2], hn[3]);
             union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               ssq_tok += hn[i] * hn[i];
-              o.s[i] = f32_to_f16_sat(hn[i] * gn[i]);
+              o.s[i] = f32_to_f16_sat(hn[i] * g4[i]);
             }
             *reinterpret_cast<u32x2*>(p.xn_out + packed_p_offset(t, n0, p.d >> 4)) = o.v;
           } else {  // PEPI_QKV
             const int rot_rows = (p.Hq + p.Hkv) * p.hd;
             const int head = n0 / p.hd, c0 = n0 % p.hd;
             if (n0 < rot_rows) {
+              const f32x4 cs = pre[rb][q4];  // (cos, sin) of the two rotary pairs held here
 #pragma unroll
               for (int pr = 0; pr < 2; ++pr) {
-                float2 cs = p.rope[(int64_t)pos * (p.hd / 2) + (c0 >> 1) + pr];
                 float a = v4[2 * pr], b = v4[2 * pr + 1];
-                v4[2 * pr] = a * cs.x - b * cs.y;
-                v4[2 * pr + 1] = b * cs.x + a * cs.y;
+                v4[2 * pr] = a * cs[2 * pr] - b * cs[2 * pr + 1];
+                v4[2 * pr + 1] = b * cs[2 * pr] + a * cs[2 * pr + 1];
               }
             }
             union { uint16_t s[4]; u32x2 v; } o;
@@ -377,14 +429,14 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     }
     if constexpr (EPI == PEPI_RESID) {
       ssq_tok += __shfl_xor(ssq_tok, 32);  // the two lane halves hold different rows of the same token
-      if (lane < 32) red_ssq[wn][wt * 128 + tb * 32 + lane] = ssq_tok;
+      if (lane < 32) red_ssq[wn][wt * 128 + tb * 32 + lane] = ssq_tok;  // (slots of tokens past the end are never read)
     }
   }
   if constexpr (EPI == PEPI_RESID) {
     // per (row tile, token) sum of squares of the new residual, the two row halves added in a fixed order
     __syncthreads();
     const int t = t_tile + tid;
-    if (t < p.T) p.ssq_out[(int64_t)rt * p.ssq_stride + t] = red_ssq[0][tid] + red_ssq[1][tid];
+    if (t < p.T) p.ssq_out[(int64_t)t * PSSQ + rt] = red_ssq[0][tid] + red_ssq[1][tid];
   }
 }
 
@@ -631,7 +683,6 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
   int32_t* cum = m->meta + 16;
   hipLaunchKernelGGL(prefill_meta_kernel, dim3(1), dim3(1024), 0, st, tok, qlens, lens, batch, T, m->row_seq, m->row_pos, m->tile_seq,
                      m->tile_q0, m->meta, m->last_tok, cum);
-  const int64_t sstride = ((int64_t)m->maxT + 255) / 256 * 256;
   if (m->cfg.weight_dtype == WWW_DTYPE_F32)
     hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(T), dim3(256), 0, st, tok, (const float*)m->embed, d, m->layers[0].attn_norm, m->hp,
                        (uint16_t*)m->xn, m->ssq_p);
@@ -648,7 +699,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
-      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.ssq_stride = sstride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
+      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
       launch_pgemm<PEPI_QKV>(p, st);
@@ -659,14 +710,14 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;
-      p.hp = m->hp; p.d = d; p.gain_next = w.ffn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p; p.ssq_stride = sstride;
+      p.hp = m->hp; p.d = d; p.gain_next = w.ffn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
       launch_pgemm<PEPI_RESID>(p, st);
       n_ssq = n_rt_d;
     }
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
-      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.ssq_stride = sstride; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
+      p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
       launch_pgemm<PEPI_SWIGLU>(p, st);
     }
@@ -674,7 +725,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
       PGemmP p = {};
       p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
       p.hp = m->hp; p.d = d; p.gain_next = m->layers[l + 1].attn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
-      p.ssq_stride = sstride;
+     
       launch_pgemm<PEPI_RESID>(p, st);
     }
   }
