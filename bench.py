@@ -12,7 +12,16 @@ a HIP graph, tokens fed back on the device).  Prints ONE JSON line:
   roofline_decode_step / roofline_prefill   whole-phase figures from the timed region
   cpu_baseline        the CPU oracle timed on a bounded sample of the same decode workload
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny]
+Two composite workloads print the same kind of line with their own phases:
+  --workload duel    one duel-and-judge round (Sec. 4.2): 32 prompts of 768 tokens answered with 256 greedy tokens by a
+                     1B-shaped and an 8B-shaped model resident together, then the 8B-shaped judge's prefill over
+                     prompt + answer A + answer B; the five phases are timed separately, `value` is the round's time
+  --workload mixed   128 sequences with Zipf(1.2) lengths in [256, 16384] on the 8B-shaped model: 512-token prefill chunks
+                     (8192-token budget per call) interleaved with decode steps over the sequences whose prompt is
+                     complete, block tables scattered over a KV pool of 90 % of the memory left beside the weights;
+                     `value` is the schedule's wall time, the two call classes are reported beside it
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed]
 """
 from __future__ import annotations
 
@@ -92,22 +101,289 @@ def decode_step_bytes(shape, ctx_lens, batch):
     return sum(per[k] * mult[k] for k in per if k != "argmax")
 
 
-def prefill_flops(shape, lens):
-    """Flops of the prefill as this method performs it: all layers' QKV projections and attention for every
-    prompt token, O / gate-up / down projections for all layers but the last (the last layer's output is only
-    needed at the final position), plus one full single-token pass and the output head per sequence."""
+def prefill_call_flops(shape, q_lens, seq_lens):
+    """Flops of one www_prefill call as this method performs it, over chunks of q new tokens whose sequences then hold seq
+    tokens (cached prefix P = seq - q): all layers' QKV projections and attention (prefix plus the chunk's own causal
+    triangle) for every new token, O / gate-up / down projections for all layers but the last (the last layer's output
+    is only needed at a chunk's final position), plus one full single-token pass and the output head per sequence."""
     d, F, V, L = shape.d_model, shape.ffn_dim, shape.vocab, shape.n_layers
     hd, Hq = shape.head_dim, shape.n_q_heads
     QD, KD = Hq * hd, shape.n_kv_heads * hd
-    T, B = float(np.sum(lens)), len(lens)
+    q = np.asarray(q_lens, np.float64)
+    P = np.asarray(seq_lens, np.float64) - q
+    T, B = float(q.sum()), len(q)
     qkv = 2 * (QD + 2 * KD) * d
     rest = 2 * (d * QD + 3 * F * d)
-    attn_layers = L - 1
-    S = np.asarray(lens, np.float64)
-    attn = 2 * Hq * hd * float(np.sum(S * S + S)) * attn_layers
+    attn = 2 * Hq * hd * float(np.sum(q * (2 * P + q + 1))) * (L - 1)
     bulk = T * (qkv * L + rest * (L - 1)) + attn
-    last = B * ((qkv + rest) * L + 2 * V * d) + 2 * 2 * Hq * hd * float(np.sum(S)) * L
+    last = B * ((qkv + rest) * L + 2 * V * d) + 2 * 2 * Hq * hd * float(np.sum(P + q)) * L
     return bulk + last
+
+
+def prefill_flops(shape, lens):
+    """Flops of a prefill of whole prompts (no cached prefix)."""
+    return prefill_call_flops(shape, lens, lens)
+
+
+def _common_fields(args, workload_text):
+    return {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+            "data": "synthetic", "config": {"workload": workload_text}}
+
+
+def bench_duel(args):
+    """One duel-and-judge round (Sec. 4.2): two executors answer the same prompts, the judge reads both answers."""
+    import torch
+    from paper_2603_20661_amd import binding as B
+    from paper_2603_20661_amd import synth
+
+    n_seq, plen = 32, 768
+    nsteps = 256 if args.decode_steps is None else args.decode_steps
+    jlen = plen + 2 * nsteps
+    lens = np.full(n_seq, plen, np.int32)
+    prompts = synth.tokens(12345, n_seq * plen, 32000).reshape(n_seq, plen)     # ids valid for both vocabularies
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    execs = {}
+    with torch.cuda.stream(stream):
+        for name, shape in (("1b", synth.M1B), ("8b", synth.M8B)):
+            t0 = time.time()
+            blob = synth.make_blob(shape)
+            log(f"duel: {name} weights {blob.size / 2**30:.2f} GiB generated in {time.time() - t0:.1f} s")
+            cap = [plen + nsteps + 1] * n_seq + ([jlen] * n_seq if name == "8b" else [])   # the 8B model is also the judge
+            cap = np.asarray(cap, np.int64)
+            mbs = int((cap.max() + 15) // 16)
+            nb = int(((cap + 15) // 16).sum()) + 64
+            table = synth.block_tables(shape.seed, cap, nb, mbs, permute=True)
+            cfg = B.make_config(shape, n_seq, mbs, n_seq * max(plen, jlen if name == "8b" else 0), nb)
+            blob_dev = torch.from_numpy(blob).to(dev)
+            model = B.Model(cfg, blob_dev, stream=stream)
+            stream.synchronize()
+            del blob_dev, blob
+            torch.cuda.empty_cache()
+            execs[name] = {"shape": shape, "model": model, "table": i32(table[:n_seq]), "judge_table": i32(table[n_seq:]),
+                           "answers": torch.zeros((nsteps, n_seq), dtype=torch.int32, device=dev),
+                           "cur": torch.empty(n_seq, dtype=torch.int32, device=dev),
+                           "logits": torch.empty((n_seq, shape.vocab), dtype=torch.float32, device=dev)}
+        prompts_dev, lens_dev, seq_dev = i32(prompts), i32(lens), i32(lens)
+        jl_dev = i32(np.full(n_seq, jlen))
+        judge_logits = execs["8b"]["logits"]
+        judge_next = torch.empty(n_seq, dtype=torch.int32, device=dev)
+
+        def one_round():
+            marks = [ev()]
+            marks[0].record(stream)
+            for name in ("1b", "8b"):
+                x = execs[name]
+                seq_dev.copy_(lens_dev)
+                B.www_prefill(x["model"], prompts_dev.view(-1), lens_dev, seq_dev, x["table"], logits=None, next_tokens=x["cur"], stream=stream)
+                marks.append(ev()); marks[-1].record(stream)
+                for s in range(nsteps):
+                    x["answers"][s].copy_(x["cur"])         # the answer leaves the loop token by token
+                    seq_dev.add_(1)
+                    B.www_decode_step(x["model"], x["cur"], seq_dev, x["table"], logits=x["logits"], next_tokens=x["cur"], stream=stream)
+                marks.append(ev()); marks[-1].record(stream)
+            judge_in = torch.cat([prompts_dev, execs["1b"]["answers"].t(), execs["8b"]["answers"].t()], dim=1).contiguous()
+            B.www_prefill(execs["8b"]["model"], judge_in.view(-1), jl_dev, jl_dev, execs["8b"]["judge_table"], logits=judge_logits,
+                          next_tokens=judge_next, stream=stream)
+            marks.append(ev()); marks[-1].record(stream)
+            return marks
+
+        for _ in range(args.warmup):
+            one_round()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall0 = time.time()
+        rounds = [one_round() for _ in range(args.steps)]
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.time() - wall0
+        ms = np.array([[a.elapsed_time(b) for a, b in zip(m[:-1], m[1:])] for m in rounds]).mean(axis=0)
+        assert torch.isfinite(judge_logits).all(), "non-finite judge logits"
+        checksum = int(judge_next.cpu().numpy().astype(np.int64).sum())
+
+    phases = {}
+    for k, name in enumerate(("1b", "8b")):
+        shape = execs[name]["shape"]
+        pre, dec = float(ms[2 * k]), float(ms[2 * k + 1])
+        pf = prefill_flops(shape, lens)
+        step_bytes = float(np.mean([decode_step_bytes(shape, lens + s + 1, n_seq) for s in range(max(nsteps, 1))]))
+        gbs = step_bytes * nsteps / (dec * 1e-3) / 1e9 if nsteps else 0.0
+        phases[f"executor_{name}_prefill"] = {"ms": round(pre, 3), "tokens_per_s": round(n_seq * plen / (pre * 1e-3), 1),
+                                              "TFLOPs": round(pf / (pre * 1e-3) / 1e12, 1), "frac_mfma_peak": round(pf / (pre * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}
+        phases[f"executor_{name}_decode"] = {"ms": round(dec, 3), "ms_per_step": round(dec / max(nsteps, 1), 4),
+                                             "tokens_per_s": round(n_seq * nsteps / (dec * 1e-3), 1), "GBps": round(gbs, 1),
+                                             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_step": int(step_bytes)}
+    jf = prefill_flops(synth.M8B, np.full(n_seq, jlen))
+    jms = float(ms[4])
+    phases["judge_prefill"] = {"ms": round(jms, 3), "tokens_per_s": round(n_seq * jlen / (jms * 1e-3), 1),
+                               "TFLOPs": round(jf / (jms * 1e-3) / 1e12, 1), "frac_mfma_peak": round(jf / (jms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)}
+    out = {"metric": "duel_round_seconds", "value": round(float(ms.sum()) * 1e-3, 4), "unit": "s", "higher_is_better": False,
+           "ms_per_step": round(float(ms.sum()), 3)}
+    out.update(_common_fields(args, f"duel-and-judge round: {n_seq} prompts of {plen} tokens, {nsteps} greedy tokens each by a 1B-shaped "
+                                    f"(seed 1) and an 8B-shaped (seed 2) model resident together, judge prefill by the 8B-shaped "
+                                    f"model over {jlen} tokens per sequence; KV block 16, random-init weights"))
+    out.update({"phases": phases, "wall_s_timed_region": round(wall, 3), "checksum_judge_tokens": checksum})
+    print(json.dumps(out), flush=True)
+    for x in execs.values():
+        x["model"].close()
+
+
+def mixed_schedule(lens, n_seq, chunk, budget, dec_steps):
+    """The interleaved schedule of the long-context mixed batch, as a list of calls: ("prefill", ids, q, seq_after) with
+    chunks of up to `chunk` tokens dealt round-robin to the sequences still prefilling within `budget` tokens per call, each
+    followed by ("decode", ids, seq_after) over the sequences whose prompt is complete, until every one has `dec_steps`."""
+    done = np.zeros(n_seq, np.int64)
+    ndec = np.zeros(n_seq, np.int64)
+    rr, calls = 0, []
+    while (ndec < dec_steps).any():
+        pending = [b for b in list(range(rr, n_seq)) + list(range(rr)) if done[b] < lens[b]]
+        pick, left = [], budget
+        for b in pending:
+            q = int(min(chunk, lens[b] - done[b]))
+            if q > left:
+                break
+            pick.append((b, q))
+            left -= q
+        if pick:
+            rr = (pick[-1][0] + 1) % n_seq
+            ids = np.array([b for b, _ in pick])
+            q = np.array([q for _, q in pick], np.int64)
+            calls.append(("prefill", ids, q, done[ids] + q, done[ids].copy()))
+            done[ids] += q
+        ids = np.nonzero((done == lens) & (ndec < dec_steps))[0]
+        if len(ids):
+            calls.append(("decode", ids, None, lens[ids] + ndec[ids] + 1, None))
+            ndec[ids] += 1
+    return calls
+
+
+def bench_mixed(args):
+    """Long-context mixed batch: chunked prefill interleaved with decode steps on the 8B-shaped model."""
+    import torch
+    from paper_2603_20661_amd import binding as B
+    from paper_2603_20661_amd import synth
+
+    shape = synth.M8B
+    n_seq, chunk, budget = 128, 512, 8192
+    dec_steps = 64 if args.decode_steps is None else args.decode_steps
+    lens = synth.lengths_zipf(2, n_seq, 1.2, 256, 16384).astype(np.int64)
+    cap = lens + dec_steps + 1
+    mbs = int((cap.max() + 15) // 16)
+    calls = mixed_schedule(lens, n_seq, chunk, budget, dec_steps)
+    prompts = [synth.tokens(1000 + b, int(lens[b]), shape.vocab) for b in range(n_seq)]
+
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).to(dev)
+    i64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int64)).to(dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t0 = time.time()
+    blob = synth.make_blob(shape)
+    log(f"mixed: weights {blob.size / 2**30:.2f} GiB generated in {time.time() - t0:.1f} s; {len(calls)} calls, "
+        f"{int(lens.sum())} prompt tokens, longest {int(lens.max())}")
+    with torch.cuda.stream(stream):
+        blob_dev = torch.from_numpy(blob).to(dev)
+        # KV pool: 90 % of the memory that is free once the weights (the blob and its packed copy) are resident
+        probe = B.make_config(shape, n_seq, mbs, budget, 1)
+        _, _, ws_bytes = B.www_query_sizes(probe)
+        free_bytes, _ = torch.cuda.mem_get_info()
+        block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * shape.head_dim * 2
+        nb = int(0.90 * (free_bytes - ws_bytes)) // block_bytes
+        table = synth.block_tables(2, cap, nb, mbs, permute=True)
+        cfg = B.make_config(shape, n_seq, mbs, budget, nb)
+        model = B.Model(cfg, blob_dev, stream=stream)
+        stream.synchronize()
+        del blob_dev, blob
+        table_dev = i32(table)
+        # per-call arguments, resident before the timed region; decode calls go through fixed staging buffers so that a
+        # step of a given batch size finds its captured graph again
+        prepared = []
+        for kind, ids, q, seq_after, done_before in calls:
+            c = {"kind": kind, "n": len(ids), "ids": i64(ids), "seq": i32(seq_after)}
+            if kind == "prefill":
+                c["tokens"] = i32(np.concatenate([prompts[b][d0: d0 + qq] for b, qq, d0 in zip(ids, q, done_before)]))
+                c["q"] = i32(q)
+                c["table"] = table_dev[c["ids"]].contiguous()
+                fin = np.nonzero(seq_after == lens[ids])[0]
+                c["fin_rows"], c["fin_ids"] = i64(fin), i64(ids[fin])
+                c["flops"] = prefill_call_flops(shape, q, seq_after)
+                c["ntok"] = int(q.sum())
+            else:
+                c["bytes"] = decode_step_bytes(shape, seq_after, len(ids))
+            prepared.append(c)
+        last_tok = torch.zeros(n_seq, dtype=torch.int32, device=dev)
+        pre_next = torch.empty(n_seq, dtype=torch.int32, device=dev)
+        dec_tok = torch.empty(n_seq, dtype=torch.int32, device=dev)
+        dec_seq = torch.empty(n_seq, dtype=torch.int32, device=dev)
+        dec_table = torch.empty((n_seq, mbs), dtype=torch.int32, device=dev)
+        logits = torch.empty((n_seq, shape.vocab), dtype=torch.float32, device=dev)
+
+        def one_pass():
+            marks = []
+            for c in prepared:
+                n = c["n"]
+                e0, e1 = ev(), ev()
+                if c["kind"] == "prefill":
+                    e0.record(stream)
+                    B.www_prefill(model, c["tokens"], c["q"], c["seq"], c["table"], logits=None, next_tokens=pre_next[:n], stream=stream)
+                    e1.record(stream)
+                    if c["fin_ids"].numel():
+                        last_tok.index_copy_(0, c["fin_ids"], pre_next[:n].index_select(0, c["fin_rows"]))
+                else:
+                    torch.index_select(last_tok, 0, c["ids"], out=dec_tok[:n])
+                    torch.index_select(table_dev, 0, c["ids"], out=dec_table[:n])
+                    dec_seq[:n].copy_(c["seq"])
+                    e0.record(stream)
+                    B.www_decode_step(model, dec_tok[:n], dec_seq[:n], dec_table[:n], logits=logits[:n], next_tokens=dec_tok[:n], stream=stream)
+                    e1.record(stream)
+                    last_tok.index_copy_(0, c["ids"], dec_tok[:n])
+                marks.append((e0, e1))
+            return marks
+
+        for _ in range(args.warmup):
+            one_pass()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        walls, per_call = [], np.zeros(len(prepared))
+        for _ in range(args.steps):
+            t0 = time.time()
+            marks = one_pass()
+            stream.synchronize()
+            torch.cuda.synchronize()
+            walls.append(time.time() - t0)
+            per_call += np.array([a.elapsed_time(b) for a, b in marks])
+        per_call /= args.steps
+        assert torch.isfinite(logits).all(), "non-finite logits"
+        checksum = int(last_tok.cpu().numpy().astype(np.int64).sum())
+
+    pre = [(c, t) for c, t in zip(prepared, per_call) if c["kind"] == "prefill"]
+    dec = [(c, t) for c, t in zip(prepared, per_call) if c["kind"] == "decode"]
+    pre_ms, dec_ms = sum(t for _, t in pre), sum(t for _, t in dec)
+    pre_tf = sum(c["flops"] for c, _ in pre) / (pre_ms * 1e-3) / 1e12
+    dec_gbs = sum(c["bytes"] for c, _ in dec) / (dec_ms * 1e-3) / 1e9
+    full = [(c, t) for c, t in dec if c["n"] == n_seq]
+    classes = {
+        "prefill_chunks": {"calls": len(pre), "ms": round(pre_ms, 2), "tokens_per_s": round(sum(c["ntok"] for c, _ in pre) / (pre_ms * 1e-3), 1),
+                           "TFLOPs": round(pre_tf, 1), "frac_mfma_peak": round(pre_tf / MFMA_PEAK_TFLOPS, 4)},
+        "decode_steps": {"calls": len(dec), "ms": round(dec_ms, 2), "tokens_per_s": round(sum(c["n"] for c, _ in dec) / (dec_ms * 1e-3), 1),
+                         "GBps": round(dec_gbs, 1), "frac_hbm_peak": round(dec_gbs / HBM_PEAK_GBS, 4)},
+    }
+    if full:
+        fb, ft = sum(c["bytes"] for c, _ in full), sum(t for _, t in full)
+        classes["decode_steps_all_128_active"] = {"calls": len(full), "ms_per_step": round(ft / len(full), 3),
+                                                  "algorithmic_bytes_per_step": int(fb / len(full)),
+                                                  "GBps": round(fb / (ft * 1e-3) / 1e9, 1), "frac_hbm_peak": round(fb / (ft * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    wall = float(np.mean(walls))
+    out = {"metric": "schedule_wall_seconds", "value": round(wall, 4), "unit": "s", "higher_is_better": False, "ms_per_step": round(wall * 1e3, 3)}
+    out.update(_common_fields(args, f"long-context mixed batch on the 8b-shaped decoder: {n_seq} sequences, Zipf(1.2) lengths "
+                                    f"{int(lens.min())}..{int(lens.max())} (sum {int(lens.sum())}), {chunk}-token prefill chunks within {budget} "
+                                    f"tokens per call interleaved with decode steps, {dec_steps} greedy tokens per sequence, KV pool "
+                                    f"{nb} blocks = {nb * block_bytes / 2**30:.0f} GiB with permuted block tables"))
+    out.update({"call_classes": classes, "kv_pool_GiB": round(nb * block_bytes / 2**30, 1), "checksum_last_tokens": checksum})
+    print(json.dumps(out), flush=True)
+    model.close()
 
 
 def main():
@@ -115,13 +391,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b"])
+    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (sequences are independent, nothing is sharded); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "duel":
+        return bench_duel(args)
+    if args.workload == "mixed":
+        return bench_mixed(args)
 
     import torch
     from paper_2603_20661_amd import binding as B

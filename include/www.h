@@ -113,7 +113,9 @@ int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_t* q_lens_d
  *   next_tokens_dev  int32 [batch] greedy next token; may be NULL
  * The step is replayed from a captured HIP graph keyed on (batch, pointers, stream); lengths, tables
  * and tokens are read from device memory at run time, so the same arrays can be updated in place
- * between steps.  batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY, HIP, STALE. */
+ * between steps.  A model keeps up to 128 captured steps (the oldest is dropped); a caller whose batch
+ * changes from step to step should pass the same staging arrays every time so that each batch size is
+ * captured once.  batch == 0 is a no-op.  Errors: INVALID_ARG, CAPACITY, HIP, STALE. */
 int www_decode_step(www_model* m, const int32_t* last_tokens_dev, const int32_t* seq_lens_dev, const int32_t* block_table_dev,
                     int32_t batch, float* logits_dev, int32_t* next_tokens_dev, void* hip_stream);
 

@@ -18,6 +18,10 @@ int decode_MT(int batch);
 
 static thread_local char g_err[512] = "";
 
+// Captured decode steps kept per model, one per (batch, argument pointers, stream); a serving loop whose batch grows and
+// shrinks one sequence at a time passes through about a hundred batch sizes.
+static const int MAX_GRAPHS = 128;
+
 // Benchmark hook: while enabled, decode steps run eagerly and an event is recorded in front of every
 // kernel; the elapsed time between consecutive events is charged to the class of the kernel in between.
 struct DecodeProfiler {
@@ -241,7 +245,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->QKVN = s.QKVN; m->QD = s.QD; m->KD = s.KD; m->max_pos = s.max_pos; m->maxB = s.maxB; m->MTmax = s.MTmax; m->maxT = s.maxT;
   m->wsplit = s.wsplit;
   m->layers = new LayerW[s.L];
-  m->graphs = new GraphEntry[16];
+  m->graphs = new GraphEntry[MAX_GRAPHS];
   m->n_graphs = 0;
   const char* env = getenv("WWW_NO_GRAPH");
   m->use_graph = !(env && env[0] == '1');
@@ -382,10 +386,10 @@ WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, con
   hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   if (ei != hipSuccess) { set_error("hipGraphInstantiate failed: %s", hipGetErrorString(ei)); return WWW_E_HIP; }
-  if (m->n_graphs == 16) {  // evict the oldest
+  if (m->n_graphs == MAX_GRAPHS) {  // evict the oldest
     (void)hipGraphExecDestroy(m->graphs[0].exec);
-    memmove(&m->graphs[0], &m->graphs[1], 15 * sizeof(GraphEntry));
-    m->n_graphs = 15;
+    memmove(&m->graphs[0], &m->graphs[1], (MAX_GRAPHS - 1) * sizeof(GraphEntry));
+    m->n_graphs = MAX_GRAPHS - 1;
   }
   GraphEntry& g = m->graphs[m->n_graphs++];
   g.batch = batch; g.tok = last_tokens_dev; g.lens = seq_lens_dev; g.table = block_table_dev; g.logits = logits_dev; g.next = next_tokens_dev;
