@@ -446,6 +446,9 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 // S^T = K Q^T / O^T = V^T P^T for its GH heads.  The keys and values of a pair of blocks (32 keys) are
 // copied into LDS once per workgroup and read from there by the four wavefronts (the cache already stores them
 // in MFMA operand order, so the copy is verbatim); the next pair travels from memory while this one is used.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
 template <int HD, int GH>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
                                                             const uint16_t* __restrict__ vplane, const int32_t* __restrict__ q_lens,
@@ -522,7 +525,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
 #pragma unroll
     for (int i = 0; i < NLD; ++i) kv[buf][tid + i * 256] = stg[i];
   };
-  auto compute = [&](int buf, int pr) __attribute__((always_inline)) {
+  // masked = false: every key of the pair is visible to every query of the wavefront (the pair ends at or before its
+  // first query position), so neither the scores nor the values need a mask; that is the case for all pairs but the
+  // last one to three of a wavefront.  The argument is a literal at both call sites.
+  auto compute = [&](int buf, int pr, const bool masked) __attribute__((always_inline)) {
     const int base = pr * 32;
     u32x4 kf0[NKF], kf1[NKF];
     u32x2 vf0[NVF], vf1[NVF];
@@ -533,12 +539,6 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
       kf0[f] = kv[buf][f * 64 + lane];
       kf1[f] = kv[buf][CH + f * 64 + lane];
     }
-    // slots past the end of the sequence may hold anything: keep them out of the MFMA (masks are all-ones elsewhere)
-    const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
-    const uint32_t a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
-    const uint32_t a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
-    const uint32_t b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
-    const uint32_t b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
       vf0[f] = v0p[f * 64 + lane];
@@ -559,16 +559,20 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
         s0[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qf[hh][f], s0[hh], 0, 0, 0);
         s1[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qf[hh][f], s1[hh], 0, 0, 0);
       }
+    // scores in units of log2; hidden keys (later than the query, or slots past the end of the sequence, which may hold
+    // anything) become -inf.  The products are formed first: a maximum of values that come straight out of an MFMA
+    // would be preceded by one quieting instruction per operand.
     float sc[GH][8], mx[GH];
 #pragma unroll
     for (int hh = 0; hh < GH; ++hh) {
-      mx[hh] = NEG_INF;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        sc[hh][i] = (base + 4 * g + i <= qpos) ? s0[hh][i] * scale_log2 : NEG_INF;
-        sc[hh][4 + i] = (base + 16 + 4 * g + i <= qpos) ? s1[hh][i] * scale_log2 : NEG_INF;
-        mx[hh] = fmaxf(mx[hh], fmaxf(sc[hh][i], sc[hh][4 + i]));
+        const float a = s0[hh][i] * scale_log2, c = s1[hh][i] * scale_log2;
+        sc[hh][i] = (!masked || base + 4 * g + i <= qpos) ? a : NEG_INF;
+        sc[hh][4 + i] = (!masked || base + 16 + 4 * g + i <= qpos) ? c : NEG_INF;
       }
+      const float m012 = fmaxf(fmaxf(sc[hh][0], sc[hh][1]), sc[hh][2]), m345 = fmaxf(fmaxf(sc[hh][3], sc[hh][4]), sc[hh][5]);
+      mx[hh] = fmaxf(fmaxf(m012, m345), fmaxf(sc[hh][6], sc[hh][7]));
     }
 #pragma unroll
     for (int hh = 0; hh < GH; ++hh) mx[hh] = fmaxf(mx[hh], __shfl_xor(mx[hh], 16));
@@ -577,12 +581,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
     f16x8 pbv[GH];
 #pragma unroll
     for (int hh = 0; hh < GH; ++hh) {
+      const float mxs = mx[hh];
       // m_run is a reference point for the exponentials, not necessarily the running maximum: the result o / l does
       // not depend on it.  It is moved (and o, l rescaled) only when a score exceeds it by more than 2^8, so that
-      // probabilities stay below 256 in fp16; after the first pairs of a sequence that is rare, and the 4 * NVF
-      // accumulator registers per head are then left alone.
-      if (__any(mx[hh] > m_run[hh] + 8.f)) {
-        const float m_new = fmaxf(m_run[hh], mx[hh]);
+      // probabilities stay below 256 in fp16 (no saturation needed in the conversion); after the first pairs of a
+      // sequence that is rare, and the 4 * NVF accumulator registers per head are then left alone.
+      if (__any(mxs > m_run[hh] + 8.f)) {
+        const float m_new = fmaxf(m_run[hh], mxs);
         // a query whose visible keys all lie in later pairs has m_new = -inf here: keep its state untouched
         const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - ((m_new == NEG_INF) ? 0.f : m_new));
         l_run[hh] *= alpha;
@@ -593,20 +598,32 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
         }
       }
       const float m_use = (m_run[hh] == NEG_INF) ? 0.f : m_run[hh];
-      union { uint16_t s[8]; f16x8 v; } pb;
+      float pv[8];
       float psum = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        float pv = __builtin_amdgcn_exp2f(sc[hh][i] - m_use);
-        psum += pv;
-        pb.s[i] = f32_to_f16_sat(pv);
+        pv[i] = __builtin_amdgcn_exp2f(sc[hh][i] - m_use);
+        psum += pv[i];
       }
       l_run[hh] += psum;
-      pbv[hh] = pb.v;
+      // two values per conversion instruction, round to nearest even
+      const f16x2 h01 = __builtin_convertvector((f32x2){pv[0], pv[1]}, f16x2), h23 = __builtin_convertvector((f32x2){pv[2], pv[3]}, f16x2);
+      const f16x2 h45 = __builtin_convertvector((f32x2){pv[4], pv[5]}, f16x2), h67 = __builtin_convertvector((f32x2){pv[6], pv[7]}, f16x2);
+      pbv[hh] = __builtin_shufflevector(__builtin_shufflevector(h01, h23, 0, 1, 2, 3), __builtin_shufflevector(h45, h67, 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    // slots past the end of the sequence may hold anything: keep them out of the MFMA (masks are all-ones elsewhere)
+    uint32_t a01 = 0xFFFFFFFFu, a23 = 0xFFFFFFFFu, b01 = 0xFFFFFFFFu, b23 = 0xFFFFFFFFu;
+    if (masked) {
+      const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
+      a01 = (ka + 0 < ctx ? 0xFFFFu : 0u) | (ka + 1 < ctx ? 0xFFFF0000u : 0u);
+      a23 = (ka + 2 < ctx ? 0xFFFFu : 0u) | (ka + 3 < ctx ? 0xFFFF0000u : 0u);
+      b01 = (kb2 + 0 < ctx ? 0xFFFFu : 0u) | (kb2 + 1 < ctx ? 0xFFFF0000u : 0u);
+      b23 = (kb2 + 2 < ctx ? 0xFFFFu : 0u) | (kb2 + 3 < ctx ? 0xFFFF0000u : 0u);
     }
 #pragma unroll
     for (int f = 0; f < NVF; ++f) {
-      const u32x4 a = {vf0[f].x & a01, vf0[f].y & a23, vf1[f].x & b01, vf1[f].y & b23};
+      const u32x4 a = masked ? u32x4{vf0[f].x & a01, vf0[f].y & a23, vf1[f].x & b01, vf1[f].y & b23}
+                             : u32x4{vf0[f].x, vf0[f].y, vf1[f].x, vf1[f].y};
 #pragma unroll
       for (int hh = 0; hh < GH; ++hh)
         oacc[hh][f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pbv[hh], oacc[hh][f], 0, 0, 0);
@@ -622,7 +639,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
     request();          // pair pr + 1
     fetch_ids(pr + 2);
     __builtin_amdgcn_sched_barrier(0);
-    if (pr < npairs) compute(pr & 1, pr);
+    if (pr < npairs) {
+      if (pr * 32 + 31 <= prefix + qw0) compute(pr & 1, pr, false);
+      else compute(pr & 1, pr, true);
+    }
     __builtin_amdgcn_sched_barrier(0);
     copy_in((pr + 1) & 1);
     __syncthreads();

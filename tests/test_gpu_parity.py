@@ -224,13 +224,15 @@ def test_capacity_and_argument_errors_on_device():
         sess.close()
 
 
-def test_8b_bench_configuration_sampled_against_oracle():
-    """The 8B-shaped workload exactly as bench.py launches it (batch 64, 80 231 prompt tokens in one prefill call,
-    then decode steps).  Properties at full size: logits finite although the pool starts as NaN, bit-identical
-    under a different physical block placement.  Sampled parity: the shortest sequence is recomputed alone by
-    the oracle (prefill + 2 decode steps) and compared with its rows of the batched GPU run."""
+@pytest.mark.parametrize("name", ["8b", "1b"])
+def test_bench_configuration_sampled_against_oracle(name):
+    """The 8B- and 1B-shaped workloads exactly as bench.py launches them (8B: batch 64, 80 231 prompt tokens in one
+    prefill call; 1B: batch 32, about 40 000 prompt tokens; then decode steps), at full depth.  Properties at full size:
+    logits finite although the pool starts as NaN, bit-identical under a different physical block placement.  Sampled
+    parity: the shortest sequence is recomputed alone by the oracle (prefill + 2 decode steps) and compared with its rows
+    of the batched GPU run."""
     from oracle import oracle as O
-    wl = synth.workload("8b")
+    wl = synth.workload(name)
     shape, lens, toks = wl.shape, wl.prompt_lens.astype(np.int32), wl.prompt_tokens
     steps = 2
     Bn = wl.batch
@@ -275,5 +277,5 @@ def test_8b_bench_configuration_sampled_against_oracle():
     ref = np.stack(o_logits)
     err = float(np.abs(got - ref).max())
     agree = float((got.argmax(-1) == ref.argmax(-1)).mean())
-    print(f"8b bench configuration, sequence {b0} (len {lens[b0]}): max|dlogit|={err:.3e} agreement={agree:.3f}", flush=True)
+    print(f"{name} bench configuration, sequence {b0} (len {lens[b0]}): max|dlogit|={err:.3e} agreement={agree:.3f}", flush=True)
     assert err <= TOL and agree == 1.0
