@@ -559,35 +559,39 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
         s0[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf0[f]), qf[hh][f], s0[hh], 0, 0, 0);
         s1[hh] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(kf1[f]), qf[hh][f], s1[hh], 0, 0, 0);
       }
-    // scores in units of log2; hidden keys (later than the query, or slots past the end of the sequence, which may hold
-    // anything) become -inf.  The products are formed first: a maximum of values that come straight out of an MFMA
-    // would be preceded by one quieting instruction per operand.
-    float sc[GH][8], mx[GH];
-#pragma unroll
-    for (int hh = 0; hh < GH; ++hh) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float a = s0[hh][i] * scale_log2, c = s1[hh][i] * scale_log2;
-        sc[hh][i] = (!masked || base + 4 * g + i <= qpos) ? a : NEG_INF;
-        sc[hh][4 + i] = (!masked || base + 16 + 4 * g + i <= qpos) ? c : NEG_INF;
-      }
-      const float m012 = fmaxf(fmaxf(sc[hh][0], sc[hh][1]), sc[hh][2]), m345 = fmaxf(fmaxf(sc[hh][3], sc[hh][4]), sc[hh][5]);
-      mx[hh] = fmaxf(fmaxf(m012, m345), fmaxf(sc[hh][6], sc[hh][7]));
-    }
-#pragma unroll
-    for (int hh = 0; hh < GH; ++hh) mx[hh] = fmaxf(mx[hh], __shfl_xor(mx[hh], 16));
-#pragma unroll
-    for (int hh = 0; hh < GH; ++hh) mx[hh] = fmaxf(mx[hh], __shfl_xor(mx[hh], 32));
+    // Softmax numerators p = 2^(score * log2(e)/sqrt(hd) - m) with a per-query reference point m (m_run) that is not
+    // necessarily the running maximum: the result o / l does not depend on it.  The common case takes no maximum at
+    // all: the exponentials are formed against the current reference, and only if some lane's sum of its eight
+    // numerators exceeds 256 (so a numerator might not fit fp16 comfortably; also true for a NaN or an infinity) or
+    // on the first pair (no reference yet) the wavefront takes the exact maxima, moves the reference up, rescales o
+    // and l and forms the exponentials again.  After the first pairs of a sequence that is rare, and the 4 * NVF
+    // accumulator registers per head are then left alone.  Hidden keys (later than the query, or slots past the end
+    // of the sequence, which may hold anything) enter as -inf and get p = 0.
     f16x8 pbv[GH];
 #pragma unroll
     for (int hh = 0; hh < GH; ++hh) {
-      const float mxs = mx[hh];
-      // m_run is a reference point for the exponentials, not necessarily the running maximum: the result o / l does
-      // not depend on it.  It is moved (and o, l rescaled) only when a score exceeds it by more than 2^8, so that
-      // probabilities stay below 256 in fp16 (no saturation needed in the conversion); after the first pairs of a
-      // sequence that is rare, and the 4 * NVF accumulator registers per head are then left alone.
-      if (__any(mxs > m_run[hh] + 8.f)) {
-        const float m_new = fmaxf(m_run[hh], mxs);
+      float sr[8];  // raw scores
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sr[i] = (!masked || base + 4 * g + i <= qpos) ? s0[hh][i] : NEG_INF;
+        sr[4 + i] = (!masked || base + 16 + 4 * g + i <= qpos) ? s1[hh][i] : NEG_INF;
+      }
+      float neg_m = (m_run[hh] == NEG_INF) ? 0.f : -m_run[hh];
+      float pv[8];
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sr[i], scale_log2, neg_m));
+        psum += pv[i];
+      }
+      if (pr == 0 || __any(!(psum <= 256.f))) {
+        float scl[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) scl[i] = sr[i] * scale_log2;
+        float mx = fmaxf(fmaxf(fmaxf(scl[0], scl[1]), fmaxf(scl[2], scl[3])), fmaxf(fmaxf(scl[4], scl[5]), fmaxf(scl[6], scl[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[hh], mx);
         // a query whose visible keys all lie in later pairs has m_new = -inf here: keep its state untouched
         const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - ((m_new == NEG_INF) ? 0.f : m_new));
         l_run[hh] *= alpha;
@@ -596,14 +600,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
         for (int f = 0; f < NVF; ++f) {
           oacc[hh][f][0] *= alpha; oacc[hh][f][1] *= alpha; oacc[hh][f][2] *= alpha; oacc[hh][f][3] *= alpha;
         }
-      }
-      const float m_use = (m_run[hh] == NEG_INF) ? 0.f : m_run[hh];
-      float pv[8];
-      float psum = 0.f;
+        neg_m = (m_new == NEG_INF) ? 0.f : -m_new;
+        psum = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pv[i] = __builtin_amdgcn_exp2f(sc[hh][i] - m_use);
-        psum += pv[i];
+        for (int i = 0; i < 8; ++i) {
+          pv[i] = __builtin_amdgcn_exp2f(scl[i] + neg_m);
+          psum += pv[i];
+        }
       }
       l_run[hh] += psum;
       // two values per conversion instruction, round to nearest even
