@@ -42,16 +42,16 @@ CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
 # HBM traffic of the dominant decode kernel class (decode_attn_kernel + decode_attn_merge_kernel), from two
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE; profiles/decode_attention_8b_traffic.md).
 # Counter units per launch, averaged over the 256 launches of those runs; scale = bytes per unit / 1024, from what the
-# same counter read for the calibration copy above (131 087.7 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
+# same counter read for the calibration copy above (131 088.1 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
 # of WRITE_SIZE for 262 144 KiB written); algorithmic bytes of those same launches for rescaling to another context.
 # Valid only for the kernel sources it was taken with: reported as null when their hash differs.
 TRAFFIC = {
     "workload": "8b", "kernel": "decode_attention",
-    "fetch_units": 163128.2 + 1674.1, "write_units": 3112.9 + 1024.0,
-    "fetch_scale": 262144.0 / 131087.7, "write_scale": 1.0,
+    "fetch_units": 163132.1 + 1674.0, "write_units": 3112.7 + 1024.0,
+    "fetch_scale": 262144.0 / 131088.1, "write_scale": 1.0,
     "algorithmic_bytes_of_measured_launches": 80383 * 4096,
     "sources": ("paper_2603_20661_amd/csrc/decode.hip", "paper_2603_20661_amd/csrc/common.h"),
-    "sha256": "939c8bdcfbb2560336996ea8f70ec4bd146804aba225cc1811b9c390dd7182b3",
+    "sha256": "9523f23b425160d3849b45e21fada3349d932ad1485bcbebb73a1ea98d19c35a",
 }
 
 
