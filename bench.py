@@ -15,7 +15,8 @@ a HIP graph, tokens fed back on the device).  Prints ONE JSON line:
 Two composite workloads print the same kind of line with their own phases:
   --workload duel    one duel-and-judge round (Sec. 4.2): 32 prompts of 768 tokens answered with 256 greedy tokens by a
                      1B-shaped and an 8B-shaped model resident together, then the 8B-shaped judge's prefill over
-                     prompt + answer A + answer B; the five phases are timed separately, `value` is the round's time
+                     prompt + answer A + answer B and the votes read off its logits; the five phases are timed
+                     separately, `value` is the round's time; the duels are then settled in the credit ledger
   --workload mixed   128 sequences with Zipf(1.2) lengths in [256, 16384] on the 8B-shaped model: 512-token prefill chunks
                      (8192-token budget per call) interleaved with decode steps over the sequences whose prompt is
                      complete, block tables scattered over a KV pool of 90 % of the memory left beside the weights;
@@ -170,6 +171,8 @@ def bench_duel(args):
         jl_dev = i32(np.full(n_seq, jlen))
         judge_logits = execs["8b"]["logits"]
         judge_next = torch.empty(n_seq, dtype=torch.int32, device=dev)
+        votes_dev = torch.empty(n_seq, dtype=torch.int32, device=dev)
+        vote_tokens = (32, 33)   # the two designated ids whose last-position logits decide a vote (any two distinct ids)
 
         def one_round():
             marks = [ev()]
@@ -187,6 +190,7 @@ def bench_duel(args):
             judge_in = torch.cat([prompts_dev, execs["1b"]["answers"].t(), execs["8b"]["answers"].t()], dim=1).contiguous()
             B.www_prefill(execs["8b"]["model"], judge_in.view(-1), jl_dev, jl_dev, execs["8b"]["judge_table"], logits=judge_logits,
                           next_tokens=judge_next, stream=stream)
+            B.www_judge_verdict(judge_logits, vote_tokens[0], vote_tokens[1], votes_dev, None, stream=stream)
             marks.append(ev()); marks[-1].record(stream)
             return marks
 
@@ -202,6 +206,16 @@ def bench_duel(args):
         ms = np.array([[a.elapsed_time(b) for a, b in zip(m[:-1], m[1:])] for m in rounds]).mean(axis=0)
         assert torch.isfinite(judge_logits).all(), "non-finite judge logits"
         checksum = int(judge_next.cpu().numpy().astype(np.int64).sum())
+        votes = votes_dev.cpu().numpy()
+    # settle the round's 32 duels in the credit ledger (host side, outside the timed region): node 0 ran the 1B executor,
+    # node 1 the 8B executor, node 2 the judge
+    ledger = B.Ledger([100.0, 100.0, 100.0], base_reward=1.0, duel_reward=0.5, duel_penalty=0.5, judge_reward=0.1)
+    for r in range(n_seq):
+        ledger.serve(r, 0)
+        ledger.serve(r, 1)
+        ledger.duel(r, 0, 1, [2], [int(votes[r])])
+    settled = {"votes_for_second_executor": int(votes.sum()), "ledger_operations": len(ledger.ops()), "stakes_after": ledger.stakes()}
+    ledger.close()
 
     phases = {}
     for k, name in enumerate(("1b", "8b")):
@@ -224,7 +238,7 @@ def bench_duel(args):
     out.update(_common_fields(args, f"duel-and-judge round: {n_seq} prompts of {plen} tokens, {nsteps} greedy tokens each by a 1B-shaped "
                                     f"(seed 1) and an 8B-shaped (seed 2) model resident together, judge prefill by the 8B-shaped "
                                     f"model over {jlen} tokens per sequence; KV block 16, random-init weights"))
-    out.update({"phases": phases, "wall_s_timed_region": round(wall, 3), "checksum_judge_tokens": checksum})
+    out.update({"phases": phases, "settlement": settled, "wall_s_timed_region": round(wall, 3), "checksum_judge_tokens": checksum})
     print(json.dumps(out), flush=True)
     for x in execs.values():
         x["model"].close()

@@ -146,6 +146,76 @@ int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floa
 int www_debug_profile(www_model* m, int32_t enable);
 int www_debug_profile_read(www_model* m, float* ms_host, int32_t* launches_host, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Duel bookkeeping (Sec. 4.2 "Duel-and-Judge Mechanism"; Sec. 5, Assumptions 2 and 3).
+ *
+ * A duel sends one request to two executors drawn by Proof-of-Stake; k judges, drawn the same way, compare the two
+ * answers; the loser forfeits part of its stake, the winner and the judges earn credit, and the outcome is recorded in
+ * the credit ledger.  The paper fixes the selection law p_i = s_i / sum_j s_j and the parameters R (base reward of a
+ * served request), R_add (reward for winning a duel) and P (penalty for losing one); how a judge's output becomes a
+ * vote, how k votes are combined, and the size of the judges' reward are not in the paper.  Chosen here:
+ *   - a judge's vote is read off its last-position logits: answer A wins iff logit[token_a] >= logit[token_b];
+ *   - the executor with more votes wins; with equal votes there is no winner and no stake moves between executors;
+ *   - the loser pays min(P, its stake) (stakes stay >= 0, Assumption 1); every judge of the duel earns judge_reward;
+ *   - draws are without replacement among nodes with a positive stake; the random numbers are the caller's.
+ * The ledger is host memory owned by the library; it is not thread-safe. */
+
+/* Votes of a judge pass.  logits_dev fp32 [batch][vocab] (as written by www_prefill); verdict_dev int32 [batch]
+ * receives 0 (answer A) or 1 (answer B); margin_dev fp32 [batch] receives logit[token_a] - logit[token_b], may be
+ * NULL.  batch == 0 is a no-op.  Errors: INVALID_ARG (tokens out of range or equal, NULL), HIP. */
+int www_judge_verdict(const float* logits_dev, int32_t batch, int32_t vocab, int32_t token_a, int32_t token_b,
+                      int32_t* verdict_dev, float* margin_dev, void* hip_stream);
+
+typedef struct www_credit_params {
+  double base_reward;  /* R: credited to an executor for every delegated request it serves */
+  double duel_reward;  /* R_add: credited to the winner of a duel */
+  double duel_penalty; /* P: taken from the loser of a duel */
+  double judge_reward; /* credited to every judge of a duel */
+} www_credit_params;
+
+#define WWW_OP_BASE_REWARD 0
+#define WWW_OP_DUEL_REWARD 1
+#define WWW_OP_DUEL_PENALTY 2
+#define WWW_OP_JUDGE_REWARD 3
+
+typedef struct www_ledger_op {
+  uint64_t request_id;
+  int32_t kind; /* WWW_OP_* */
+  int32_t node;
+  double amount;      /* signed change of the node's stake */
+  double stake_after; /* the node's stake once the operation is applied */
+} www_ledger_op;
+
+typedef struct www_ledger www_ledger;
+
+/* New ledger over n_nodes nodes with the given stakes (host array, copied; each >= 0).  Errors: INVALID_ARG. */
+int www_ledger_create(int32_t n_nodes, const double* initial_stake, const www_credit_params* params, www_ledger** out);
+void www_ledger_free(www_ledger* ledger); /* NULL is allowed */
+/* Copies the current stakes into out[n_nodes] (host). */
+int www_ledger_stakes(const www_ledger* ledger, double* out);
+
+/* k Proof-of-Stake draws without replacement (Sec. 3.2 "Executor selection"; Assumption 3: p_i = s_i / sum_j s_j
+ * over the nodes still in play).  u01[k]: the caller's uniform numbers in [0, 1); draw d picks the first node, in node
+ * order, whose running stake sum exceeds u01[d] times the total still in play; nodes in exclude[n_exclude], nodes
+ * already drawn and nodes without stake are out of play.  chosen[k] receives the node ids.  Errors: INVALID_ARG,
+ * CAPACITY (fewer staked nodes in play than draws). */
+int www_pos_sample(const www_ledger* ledger, const double* u01, int32_t k, const int32_t* exclude, int32_t n_exclude,
+                   int32_t* chosen);
+
+/* Records that `executor` served delegated request `request_id`: + base_reward. */
+int www_ledger_serve(www_ledger* ledger, uint64_t request_id, int32_t executor);
+
+/* Settles a duel: verdicts[j] in {0, 1} is judge judges[j]'s vote for executor_a (0) or executor_b (1); judges are
+ * distinct nodes other than the executors; k may be 0.  Appends, in this order: winner + duel_reward and loser
+ * - min(duel_penalty, stake) if there is a winner, then + judge_reward for every judge in the given order.
+ * *winner_out (may be NULL) receives the winning node or -1.  Errors: INVALID_ARG (nothing is applied). */
+int www_ledger_duel(www_ledger* ledger, uint64_t request_id, int32_t executor_a, int32_t executor_b, const int32_t* judges,
+                    const int32_t* verdicts, int32_t k, int32_t* winner_out);
+
+/* Number of operations recorded so far, and a copy of operations [first, first + count) into out (host). */
+int64_t www_ledger_num_ops(const www_ledger* ledger);
+int www_ledger_read_ops(const www_ledger* ledger, int64_t first, int64_t count, www_ledger_op* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libwww.so")
 ABI_VERSION = 1
 E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP, E_STALE = -1, -2, -3, -4, -5, -6
 EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_model_free", "www_last_error",
-           "www_debug_slots", "www_debug_read", "www_debug_profile", "www_debug_profile_read")
+           "www_debug_slots", "www_debug_read", "www_debug_profile", "www_debug_profile_read",
+           "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
+           "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops")
+OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
 
 class WwwConfig(ctypes.Structure):
@@ -27,6 +30,15 @@ class WwwConfig(ctypes.Structure):
                [(n, ctypes.c_uint32) for n in ("kv_block_size", "weight_dtype", "max_batch", "max_blocks_per_seq",
                                                "max_prefill_tokens", "reserved")] + \
                [("num_kv_blocks", ctypes.c_uint64)]
+
+
+class WwwCreditParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("base_reward", "duel_reward", "duel_penalty", "judge_reward")]
+
+
+class WwwLedgerOp(ctypes.Structure):
+    _fields_ = [("request_id", ctypes.c_uint64), ("kind", ctypes.c_int32), ("node", ctypes.c_int32),
+                ("amount", ctypes.c_double), ("stake_after", ctypes.c_double)]
 
 
 class WwwError(RuntimeError):
@@ -53,8 +65,21 @@ def _load_library():
     L.www_debug_read.argtypes = [vp, i32, vp, ctypes.c_uint64, vp]
     L.www_debug_profile.argtypes = [vp, i32]
     L.www_debug_profile_read.argtypes = [vp, vp, vp, vp]
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    L.www_judge_verdict.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+    L.www_ledger_create.argtypes = [i32, dp, ctypes.POINTER(WwwCreditParams), ctypes.POINTER(vp)]
+    L.www_ledger_free.argtypes = [vp]
+    L.www_ledger_free.restype = None
+    L.www_ledger_stakes.argtypes = [vp, dp]
+    L.www_pos_sample.argtypes = [vp, dp, i32, ip, i32, ip]
+    L.www_ledger_serve.argtypes = [vp, ctypes.c_uint64, i32]
+    L.www_ledger_duel.argtypes = [vp, ctypes.c_uint64, i32, i32, ip, ip, i32, ip]
+    L.www_ledger_num_ops.argtypes = [vp]
+    L.www_ledger_num_ops.restype = ctypes.c_int64
+    L.www_ledger_read_ops.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(WwwLedgerOp)]
     for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read",
-                 "www_debug_profile", "www_debug_profile_read"):
+                 "www_debug_profile", "www_debug_profile_read", "www_judge_verdict", "www_ledger_create", "www_ledger_stakes",
+                 "www_pos_sample", "www_ledger_serve", "www_ledger_duel", "www_ledger_read_ops"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -162,3 +187,59 @@ def www_debug_profile_read(model: Model, stream=None):
     n = (ctypes.c_int32 * 8)()
     _check(lib.www_debug_profile_read(model._h, ms, n, _stream(stream)))
     return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def www_judge_verdict(logits, token_a: int, token_b: int, verdict, margin=None, stream=None):
+    """logits fp32 [batch, vocab] -> verdict int32 [batch] (0: answer A, 1: answer B), margin fp32 [batch] (optional)"""
+    batch, vocab = logits.shape
+    _check(lib.www_judge_verdict(_ptr(logits, torch.float32), batch, vocab, token_a, token_b, _ptr(verdict, torch.int32),
+                                 _ptr(margin, torch.float32), _stream(stream)))
+
+
+class Ledger:
+    """Handle of a host-side credit ledger (argument marshalling only)."""
+
+    def __init__(self, stakes, base_reward, duel_reward, duel_penalty, judge_reward):
+        n = len(stakes)
+        self.n = n
+        par = WwwCreditParams(base_reward, duel_reward, duel_penalty, judge_reward)
+        h = ctypes.c_void_p()
+        _check(lib.www_ledger_create(n, (ctypes.c_double * n)(*[float(x) for x in stakes]), ctypes.byref(par), ctypes.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.www_ledger_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def stakes(self):
+        out = (ctypes.c_double * self.n)()
+        _check(lib.www_ledger_stakes(self._h, out))
+        return list(out)
+
+    def pos_sample(self, u01, exclude=()):
+        k, ne = len(u01), len(exclude)
+        chosen = (ctypes.c_int32 * max(k, 1))()
+        _check(lib.www_pos_sample(self._h, (ctypes.c_double * max(k, 1))(*[float(u) for u in u01]), k,
+                                  (ctypes.c_int32 * max(ne, 1))(*[int(e) for e in exclude]), ne, chosen))
+        return list(chosen)[:k]
+
+    def serve(self, request_id: int, executor: int):
+        _check(lib.www_ledger_serve(self._h, request_id, executor))
+
+    def duel(self, request_id: int, executor_a: int, executor_b: int, judges, verdicts) -> int:
+        k = len(judges)
+        assert len(verdicts) == k
+        winner = ctypes.c_int32(-2)
+        _check(lib.www_ledger_duel(self._h, request_id, executor_a, executor_b, (ctypes.c_int32 * max(k, 1))(*[int(j) for j in judges]),
+                                   (ctypes.c_int32 * max(k, 1))(*[int(v) for v in verdicts]), k, ctypes.byref(winner)))
+        return winner.value
+
+    def ops(self):
+        n = lib.www_ledger_num_ops(self._h)
+        out = (WwwLedgerOp * max(n, 1))()
+        _check(lib.www_ledger_read_ops(self._h, 0, n, out))
+        return [(o.request_id, o.kind, o.node, o.amount, o.stake_after) for o in out[:n]]

@@ -748,7 +748,6 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
       PGemmP p = {};
       p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
       p.hp = m->hp; p.d = d; p.gain_next = m->layers[l + 1].attn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
-     
       launch_pgemm<PEPI_RESID>(p, st);
     }
   }
