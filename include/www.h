@@ -216,6 +216,72 @@ int www_ledger_duel(www_ledger* ledger, uint64_t request_id, int32_t executor_a,
 int64_t www_ledger_num_ops(const www_ledger* ledger);
 int www_ledger_read_ops(const www_ledger* ledger, int64_t first, int64_t count, www_ledger_op* out);
 
+/* ------------------------------------------------------------------------------------------------
+ * Serving loop of one provider (App. B "Model Manager": the node polls its backend for the number of active and
+ * queued requests and the memory utilisation; App. C: target utilisation 70 %).  Host-side only; it plans which
+ * sequences go into the next www_prefill / www_decode_step calls and owns the KV blocks.  The paper treats the backend
+ * as a black box, so the policy is this library's: requests are admitted first come first served (nobody overtakes
+ * the head of the queue) while a block-table row is free and the blocks they can ever need, ceil((prompt +
+ * max_new_tokens - 1) / 16), fit under target_utilisation * num_kv_blocks (reserved at admission, so a running
+ * sequence is never evicted); each iteration feeds prompt chunks of at most chunk_tokens, round-robin over the
+ * sequences still prefilling and starting behind the last one served, until the first chunk that would exceed
+ * token_budget, and then runs one decode step over every sequence whose prompt is complete (the prefill call that
+ * completes a prompt yields the sequence's first token).  A request ends after max_new_tokens tokens; its blocks go
+ * back to the free list (last freed, first reused).  Not thread-safe. */
+typedef struct www_sched_config {
+  uint32_t max_batch;          /* sequences resident at once = rows ("slots") of the block table */
+  uint32_t max_blocks_per_seq; /* columns of the block table */
+  uint32_t token_budget;       /* new prompt tokens per iteration (<= the model's max_prefill_tokens) */
+  uint32_t chunk_tokens;       /* longest prompt chunk of one sequence per iteration */
+  uint32_t kv_block_size;      /* 16 */
+  uint32_t reserved;           /* 0 */
+  uint64_t num_kv_blocks;      /* blocks of the model's KV pool */
+  double target_utilisation;   /* in (0, 1]: share of the pool that admitted sequences may reserve */
+} www_sched_config;
+
+typedef struct www_sched_step {
+  int32_t n_prefill;        /* sequences in this iteration's www_prefill call (0: no call) */
+  int32_t n_prefill_tokens; /* sum of their chunk lengths */
+  int32_t n_decode;         /* sequences in this iteration's www_decode_step call (0: no call) */
+} www_sched_step;
+
+typedef struct www_stats {
+  uint32_t active, queued;     /* sequences holding a slot / requests waiting */
+  uint64_t finished;           /* requests completed so far */
+  uint64_t kv_blocks_reserved, kv_blocks_total;
+  double kv_utilisation;       /* reserved / total */
+  uint64_t iterations, prompt_tokens_done, tokens_generated;
+} www_stats;
+
+typedef struct www_sched www_sched;
+
+/* Errors: INVALID_ARG, BAD_CONFIG. */
+int www_sched_create(const www_sched_config* cfg, www_sched** out);
+void www_sched_free(www_sched* sched); /* NULL is allowed */
+
+/* Queues a request.  Errors: INVALID_ARG (lengths < 1), CAPACITY (it could never be admitted). */
+int www_sched_submit(www_sched* sched, uint64_t request_id, int32_t prompt_len, int32_t max_new_tokens);
+
+/* Admits what fits and plans one iteration.  All arrays are host memory with room for max_batch entries.
+ * Prefill call, entry i < n_prefill: block-table row prefill_slot[i], chunk of prefill_q_len[i] tokens taken from
+ * position prefill_prompt_offset[i] of request prefill_request[i]'s prompt, sequence length afterwards
+ * prefill_seq_len[i].  Decode call, entry i < n_decode: row decode_slot[i], length decode_seq_len[i] once the token
+ * fed to the step is appended; that token is the sequence's latest one (from this iteration's prefill call if the
+ * prompt was completed there).  The plan must be executed and committed before the next one.  Errors: INVALID_ARG. */
+int www_sched_plan(www_sched* sched, www_sched_step* step, int32_t* prefill_slot, int32_t* prefill_q_len, int32_t* prefill_seq_len,
+                   int32_t* prefill_prompt_offset, uint64_t* prefill_request, int32_t* decode_slot, int32_t* decode_seq_len,
+                   uint64_t* decode_request);
+
+/* Block-table row of a slot: row_host[max_blocks_per_seq], -1 beyond the sequence's reservation. */
+int www_sched_table_row(const www_sched* sched, int32_t slot, int32_t* row_host);
+
+/* Marks the planned iteration as executed: counters advance, requests that have all their tokens leave and are listed
+ * in finished_requests[max_batch] (*n_finished of them, in slot order).  Errors: INVALID_ARG (nothing planned). */
+int www_sched_commit(www_sched* sched, int32_t* n_finished, uint64_t* finished_requests);
+
+/* The figures a Model Manager polls. */
+int www_get_stats(const www_sched* sched, www_stats* out);
+
 #ifdef __cplusplus
 }
 #endif

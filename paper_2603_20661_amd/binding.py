@@ -19,7 +19,9 @@ E_INVALID_ARG, E_BAD_CONFIG, E_ABI_MISMATCH, E_CAPACITY, E_HIP, E_STALE = -1, -2
 EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_model_free", "www_last_error",
            "www_debug_slots", "www_debug_read", "www_debug_profile", "www_debug_profile_read",
            "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
-           "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops")
+           "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
+           "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
+           "www_get_stats")
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
 
@@ -39,6 +41,21 @@ class WwwCreditParams(ctypes.Structure):
 class WwwLedgerOp(ctypes.Structure):
     _fields_ = [("request_id", ctypes.c_uint64), ("kind", ctypes.c_int32), ("node", ctypes.c_int32),
                 ("amount", ctypes.c_double), ("stake_after", ctypes.c_double)]
+
+
+class WwwSchedConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("max_batch", "max_blocks_per_seq", "token_budget", "chunk_tokens", "kv_block_size",
+                                               "reserved")] + [("num_kv_blocks", ctypes.c_uint64), ("target_utilisation", ctypes.c_double)]
+
+
+class WwwSchedStep(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_prefill", "n_prefill_tokens", "n_decode")]
+
+
+class WwwStats(ctypes.Structure):
+    _fields_ = [("active", ctypes.c_uint32), ("queued", ctypes.c_uint32), ("finished", ctypes.c_uint64),
+                ("kv_blocks_reserved", ctypes.c_uint64), ("kv_blocks_total", ctypes.c_uint64), ("kv_utilisation", ctypes.c_double),
+                ("iterations", ctypes.c_uint64), ("prompt_tokens_done", ctypes.c_uint64), ("tokens_generated", ctypes.c_uint64)]
 
 
 class WwwError(RuntimeError):
@@ -77,9 +94,19 @@ def _load_library():
     L.www_ledger_num_ops.argtypes = [vp]
     L.www_ledger_num_ops.restype = ctypes.c_int64
     L.www_ledger_read_ops.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(WwwLedgerOp)]
+    u64a = ctypes.POINTER(ctypes.c_uint64)
+    L.www_sched_create.argtypes = [ctypes.POINTER(WwwSchedConfig), ctypes.POINTER(vp)]
+    L.www_sched_free.argtypes = [vp]
+    L.www_sched_free.restype = None
+    L.www_sched_submit.argtypes = [vp, ctypes.c_uint64, i32, i32]
+    L.www_sched_plan.argtypes = [vp, ctypes.POINTER(WwwSchedStep), ip, ip, ip, ip, u64a, ip, ip, u64a]
+    L.www_sched_table_row.argtypes = [vp, i32, ip]
+    L.www_sched_commit.argtypes = [vp, ip, u64a]
+    L.www_get_stats.argtypes = [vp, ctypes.POINTER(WwwStats)]
     for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read",
                  "www_debug_profile", "www_debug_profile_read", "www_judge_verdict", "www_ledger_create", "www_ledger_stakes",
-                 "www_pos_sample", "www_ledger_serve", "www_ledger_duel", "www_ledger_read_ops"):
+                 "www_pos_sample", "www_ledger_serve", "www_ledger_duel", "www_ledger_read_ops", "www_sched_create", "www_sched_submit",
+                 "www_sched_plan", "www_sched_table_row", "www_sched_commit", "www_get_stats"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -243,3 +270,53 @@ class Ledger:
         out = (WwwLedgerOp * max(n, 1))()
         _check(lib.www_ledger_read_ops(self._h, 0, n, out))
         return [(o.request_id, o.kind, o.node, o.amount, o.stake_after) for o in out[:n]]
+
+
+class Scheduler:
+    """Handle of a host-side continuous-batching scheduler (argument marshalling only)."""
+
+    def __init__(self, max_batch, max_blocks_per_seq, token_budget, chunk_tokens, num_kv_blocks, target_utilisation=0.7):
+        self.cfg = WwwSchedConfig(max_batch, max_blocks_per_seq, token_budget, chunk_tokens, 16, 0, num_kv_blocks, target_utilisation)
+        h = ctypes.c_void_p()
+        _check(lib.www_sched_create(ctypes.byref(self.cfg), ctypes.byref(h)))
+        self._h = h
+        n = max_batch
+        self._i = [(ctypes.c_int32 * n)() for _ in range(6)]
+        self._r = [(ctypes.c_uint64 * n)() for _ in range(3)]
+        self._row = (ctypes.c_int32 * max_blocks_per_seq)()
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.www_sched_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def submit(self, request_id: int, prompt_len: int, max_new_tokens: int):
+        _check(lib.www_sched_submit(self._h, request_id, prompt_len, max_new_tokens))
+
+    def plan(self):
+        """-> (prefill entries [(slot, q_len, seq_len, prompt_offset, request)], decode entries [(slot, seq_len, request)])"""
+        st = WwwSchedStep()
+        ps, pq, pl, po, ds, dl = self._i
+        pr, dr, _ = self._r
+        _check(lib.www_sched_plan(self._h, ctypes.byref(st), ps, pq, pl, po, pr, ds, dl, dr))
+        pre = [(ps[i], pq[i], pl[i], po[i], pr[i]) for i in range(st.n_prefill)]
+        assert sum(e[1] for e in pre) == st.n_prefill_tokens
+        return pre, [(ds[i], dl[i], dr[i]) for i in range(st.n_decode)]
+
+    def table_row(self, slot: int):
+        _check(lib.www_sched_table_row(self._h, slot, self._row))
+        return list(self._row)
+
+    def commit(self):
+        """-> requests that finished with this iteration"""
+        n = ctypes.c_int32()
+        _check(lib.www_sched_commit(self._h, ctypes.byref(n), self._r[2]))
+        return list(self._r[2][:n.value])
+
+    def stats(self) -> dict:
+        st = WwwStats()
+        _check(lib.www_get_stats(self._h, ctypes.byref(st)))
+        return {f: getattr(st, f) for f, _ in WwwStats._fields_}

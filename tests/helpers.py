@@ -60,6 +60,22 @@ class GpuSession:
         self.model.close()
 
 
+def oracle_replay(shape, blob, prompt, generated):
+    """One sequence alone through the oracle: prefill of `prompt`, then one decode step per entry of `generated`
+    (teacher-forced).  Returns logits [1 + len(generated), V]: after the prompt and after each appended token."""
+    from oracle import oracle as O
+    n = len(prompt) + len(generated)
+    m = O.OracleModel(shape, blob, max_seqs=1, max_ctx=n + 1)
+    out = []
+    lg, _, _ = m.forward(prompt, [len(prompt)], [len(prompt)], seq_ids=[0])
+    out.append(lg[0])
+    for i, t in enumerate(generated):
+        lg, _, _ = m.forward([t], [1], [len(prompt) + i + 1], seq_ids=[0])
+        out.append(lg[0])
+    m.close()
+    return np.stack(out)
+
+
 def oracle_job(shape, blob, lens, toks, steps, table, num_blocks, chunk=None):
     """Oracle: prefill (optionally in chunks) then `steps` greedy decode steps.
     Returns logits [steps+1, B, V] and the greedy tokens [steps+1, B]."""

@@ -16,7 +16,7 @@ import numpy as np
 import pytest
 
 from paper_2603_20661_amd import synth
-from helpers import GpuSession
+from helpers import GpuSession, oracle_replay
 
 pytestmark = pytest.mark.gpu
 
@@ -25,22 +25,6 @@ AGREE = 0.99
 
 WIDE8B = dataclasses.replace(synth.M8B, name="wide8b", n_layers=2, seed=31)
 WIDE1B = dataclasses.replace(synth.M1B, name="wide1b", n_layers=2, seed=32)
-
-
-def oracle_replay(shape, blob, prompt, generated):
-    """One sequence alone through the oracle: prefill of `prompt`, then one decode step per entry of `generated`
-    (teacher-forced).  Returns logits [1 + len(generated), V]: after the prompt and after each appended token."""
-    from oracle import oracle as O
-    n = len(prompt) + len(generated)
-    m = O.OracleModel(shape, blob, max_seqs=1, max_ctx=n + 1)
-    out = []
-    lg, _, _ = m.forward(prompt, [len(prompt)], [len(prompt)], seq_ids=[0])
-    out.append(lg[0])
-    for i, t in enumerate(generated):
-        lg, _, _ = m.forward([t], [1], [len(prompt) + i + 1], seq_ids=[0])
-        out.append(lg[0])
-    m.close()
-    return np.stack(out)
 
 
 def summarize(what, gpu_logits, gpu_next, ref_logits):
