@@ -25,6 +25,7 @@ _lib = None
 
 WDTYPE_F32 = 0
 WDTYPE_BF16 = 1
+WDTYPE_FP8WO = 2   # matrices as FP8 E4M3 codes with one fp32 scale per matrix; embedding bf16
 KV_BLOCK = 16
 ALIGN = 256  # every tensor of the weight blob starts on a 256-byte boundary
 
@@ -48,6 +49,8 @@ def _load():
         lib.wwwsynth_normal_bf16.argtypes = [u64, u64, u64, u64, dbl, dbl, vp]
         lib.wwwsynth_words.argtypes = [u64, u64, u64, u64, vp]
         lib.wwwsynth_uniform_i32.argtypes = [u64, u64, u64, u64, ctypes.c_uint32, vp]
+        lib.wwwsynth_encode_e4m3.argtypes = [vp, u64, dbl, vp]
+        lib.wwwsynth_encode_e4m3.restype = None
         lib.wwwsynth_mix.argtypes = [u64]
         lib.wwwsynth_mix.restype = u64
         for f in (lib.wwwsynth_normal_f32, lib.wwwsynth_normal_bf16, lib.wwwsynth_words, lib.wwwsynth_uniform_i32):
@@ -154,11 +157,14 @@ def blob_layout(shape: ModelShape):
     def add(name, rows, cols, dt):
         nonlocal off
         entries.append((name, off, rows, cols, dt))
-        nbytes = rows * cols * (4 if dt == WDTYPE_F32 else 2)
+        nbytes = rows * cols * {WDTYPE_F32: 4, WDTYPE_BF16: 2, WDTYPE_FP8WO: 1}[dt]
         off += (nbytes + ALIGN - 1) // ALIGN * ALIGN
+        if dt == WDTYPE_FP8WO:      # the matrix's scale follows it in a slot of its own
+            entries.append((name + ".scale", off, 1, 1, WDTYPE_F32))
+            off += ALIGN
 
     wd = shape.weight_dtype
-    add("embed", V, d, wd)
+    add("embed", V, d, WDTYPE_BF16 if wd == WDTYPE_FP8WO else wd)
     for l in range(shape.n_layers):
         add(f"l{l}.attn_norm", 1, d, WDTYPE_F32)
         add(f"l{l}.wqkv", shape.qkv_rows, d, wd)
@@ -174,13 +180,26 @@ def blob_layout(shape: ModelShape):
 def make_blob(shape: ModelShape, std: float = 0.02, gain_std: float = 0.0, seed=None) -> np.ndarray:
     """Random-init weight blob (uint8 array).  Matrices ~ N(0, std^2); gains = 1 + N(0, gain_std^2).
 
-    Tensor t of the table is drawn from stream id t of the model's seed.
+    Tensor t of the table is drawn from stream id t of the model's seed.  In the fp8 weight-only format a matrix is
+    drawn in fp32, its scale is max|w| / 448 (fp32) and each element is stored as the E4M3 code nearest to w / scale
+    (`wwwsynth_encode_e4m3`): the codes and scales ARE the model, both sides read them as given.
     """
     seed = shape.seed if seed is None else seed
     entries, total = blob_layout(shape)
     blob = np.zeros(total, dtype=np.uint8)
     for t, (name, off, rows, cols, dt) in enumerate(entries):
         n = rows * cols
+        if name.endswith(".scale"):
+            continue                                  # written together with its matrix
+        if dt == WDTYPE_FP8WO:
+            w = normal_f32(seed, t, n, std=std)
+            scale = np.float32(np.abs(w).max() / 448.0)
+            codes = blob[off:off + n]
+            _load().wwwsynth_encode_e4m3(w.ctypes.data, n, 1.0 / float(scale), codes.ctypes.data)
+            soff = entries[t + 1][1]
+            blob[soff:soff + 4].view(np.float32)[0] = scale
+            del w
+            continue
         if name.endswith("norm"):
             view = blob[off:off + 4 * n].view(np.float32)
             if gain_std > 0:
@@ -200,6 +219,8 @@ def blob_tensor(shape: ModelShape, blob: np.ndarray, name: str) -> np.ndarray:
     for (nm, off, rows, cols, dt) in entries:
         if nm == name:
             n = rows * cols
+            if dt == WDTYPE_FP8WO:
+                raise ValueError("fp8 matrices are not decoded here (the generators hold none of the method's arithmetic)")
             if dt == WDTYPE_F32:
                 a = blob[off:off + 4 * n].view(np.float32).copy()
             else:

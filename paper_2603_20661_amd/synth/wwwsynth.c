@@ -56,6 +56,30 @@ void wwwsynth_normal_bf16(uint64_t seed, uint64_t stream_id, uint64_t first, uin
     out[i] = f32_to_bf16_bits((float)(mean + std * normal_at(key, first + (uint64_t)i)));
 }
 
+/* fp32 -> OCP FP8 E4M3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest finite value
+ * 448 = 0x7E, 0x7F is NaN and never produced), round to nearest even, saturating.  Part of the input recipe of the
+ * fp8 weight-only configuration: the blob stores these codes, code = e4m3(value * inv_scale). */
+static inline uint8_t f32_to_e4m3(float x) {
+  uint8_t sign = signbit(x) ? 0x80 : 0x00;
+  float a = fabsf(x);
+  if (!(a < 448.f)) return sign | 0x7E; /* also catches NaN */
+  int ex;
+  (void)frexpf(a, &ex); /* a = m * 2^ex, m in [0.5, 1) */
+  int e = ex - 1;
+  if (a == 0.f || e < -6) { /* subnormal range: multiples of 2^-9; 8 of them make the smallest normal, code 0x08 */
+    return sign | (uint8_t)rintf(a * 512.f);
+  }
+  float q = rintf(ldexpf(a, 3 - e)); /* 8 .. 16 */
+  if (q == 16.f) { q = 8.f; e += 1; }
+  return sign | (uint8_t)(((e + 7) << 3) | ((int)q - 8));
+}
+
+void wwwsynth_encode_e4m3(const float* src, uint64_t n, double inv_scale, uint8_t* out) {
+  const float f = (float)inv_scale;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < (int64_t)n; ++i) out[i] = f32_to_e4m3(src[i] * f);
+}
+
 /* the bare mixing function, exported so that tests can check it against SplitMix64's published outputs */
 uint64_t wwwsynth_mix(uint64_t z) { return mix(z); }
 
