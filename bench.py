@@ -22,7 +22,10 @@ Two composite workloads print the same kind of line with their own phases:
                      complete, block tables scattered over a KV pool of 90 % of the memory left beside the weights;
                      `value` is the schedule's wall time, the two call classes are reported beside it
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed]
+  --workload 8b-fp8wo / 1b-fp8wo   the 8B / 1B jobs with the matrices stored as FP8 E4M3 codes (weight-only; arithmetic
+                     and activations unchanged); rooflines count one byte per streamed weight
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed|8b-fp8wo|1b-fp8wo]
 """
 from __future__ import annotations
 
@@ -84,14 +87,15 @@ def decode_bytes_per_class(shape, ctx_lens, batch):
     d, F, V, L = shape.d_model, shape.ffn_dim, shape.vocab, shape.n_layers
     QD, KD = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
     kv_tok_layer = 2 * KD * 2
+    wb = 1 if shape.weight_dtype == 2 else 2      # bytes per streamed weight: FP8 codes, else 16-bit
     return {
         "embed": batch * d * 2,
-        "qkv_gemm": (QD + 2 * KD) * d * 2 + batch * kv_tok_layer,     # weights + this token's K/V write
+        "qkv_gemm": (QD + 2 * KD) * d * wb + batch * kv_tok_layer,     # weights + this token's K/V write
         "decode_attention": float(np.sum(ctx_lens)) * kv_tok_layer,
-        "o_gemm": d * QD * 2,
-        "gate_up_gemm": 2 * F * d * 2,
-        "down_gemm": d * F * 2,
-        "lm_head_gemm": V * d * 2 + batch * V * 4,
+        "o_gemm": d * QD * wb,
+        "gate_up_gemm": 2 * F * d * wb,
+        "down_gemm": d * F * wb,
+        "lm_head_gemm": V * d * wb + batch * V * 4,
         "argmax": batch * V * 4,
     }, {"embed": 1, "qkv_gemm": L, "decode_attention": L, "o_gemm": L, "gate_up_gemm": L, "down_gemm": L,
         "lm_head_gemm": 1, "argmax": 1}
@@ -405,7 +409,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed"])
+    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed", "1b-fp8wo", "8b-fp8wo"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -524,7 +528,7 @@ def main():
                     "algorithmic_bytes_per_launch": int(per_bytes[dom]), "avg_launch_ms": kernels[dom]["avg_ms"]}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and shape.weight_dtype != 2:   # (the fp8 weight-only workloads are not the bench line)
         cpu = cpu_baseline(shape, blob, lens, nsteps)
 
     out = {

@@ -62,6 +62,12 @@ extern "C" {
 
 #define WWW_DTYPE_F32 0u  /* weights given in fp32: kept as two fp16 terms (hi + lo) */
 #define WWW_DTYPE_BF16 1u /* weights given in bf16: converted to fp16 (exact for |w| >= 2^-17) */
+#define WWW_DTYPE_FP8WO 2u /* weight-only FP8 (the paper's quantisation experiment, Sec. 6.3, names "fp8wo"; the format is
+                              this library's reading): every projection matrix and the output head as OCP FP8 E4M3 codes
+                              (1 byte each, row-major), each followed, on the next 256-byte boundary, by one fp32 scale in a
+                              256-byte slot; weight = value(code) * scale.  The embedding stays bf16, gains fp32, and
+                              activations and arithmetic are those of the unquantised model.  The decode path streams the
+                              codes (half the bytes) and widens them to fp16 in registers; prefill uses an fp16 copy. */
 
 typedef struct www_model www_model; /* opaque handle */
 

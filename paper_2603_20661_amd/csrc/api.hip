@@ -73,7 +73,7 @@ static int check_config(const www_config* c) {
   else if (c->n_q_heads % c->n_kv_heads) why = "n_q_heads must be a multiple of n_kv_heads";
   else if (int g = c->n_q_heads / c->n_kv_heads; g != 1 && g != 2 && g != 4 && g != 8) why = "query heads per kv head must be 1, 2, 4 or 8";
   else if (c->kv_block_size != KV_BS) why = "kv_block_size must be 16";
-  else if (c->weight_dtype > 1) why = "weight_dtype must be 0 (fp32) or 1 (bf16)";
+  else if (c->weight_dtype > 2) why = "weight_dtype must be 0 (fp32), 1 (bf16) or 2 (FP8 weight-only)";
   else if (c->max_batch == 0 || c->max_batch > 1024) why = "max_batch must be in 1..1024";
   else if (c->max_blocks_per_seq == 0 || c->num_kv_blocks == 0) why = "empty KV pool";
   else if (c->num_kv_blocks > 0x7fffffffull) why = "num_kv_blocks must fit int32";
@@ -105,6 +105,8 @@ struct Plan {
   uint64_t total;
   uint64_t embed, final_norm, lm_head, lm_head_lo, rope;
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
+  std::vector<uint64_t> wqkv8, wo8, wgu8, wd8;  // FP8 weight-only models: packed codes for the decode path
+  uint64_t lm_head8;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
   uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_hdr, attn_start, attn_pref;
   uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
@@ -113,7 +115,7 @@ struct Plan {
 
 struct Dims {
   int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, maxB, MTmax, maxT, max_pos;
-  bool wsplit;
+  bool wsplit, fp8;
 };
 
 static Dims dims_of(const www_config* c) {
@@ -124,6 +126,7 @@ static Dims dims_of(const www_config* c) {
   s.maxB = c->max_batch; s.MTmax = decode_MT(s.maxB); s.maxT = c->max_prefill_tokens;
   s.max_pos = c->max_blocks_per_seq * KV_BS;
   s.wsplit = c->weight_dtype == WWW_DTYPE_F32;
+  s.fp8 = c->weight_dtype == WWW_DTYPE_FP8WO;
   return s;
 }
 
@@ -134,8 +137,11 @@ static void make_plan(const www_config* c, Plan& p) {
   const uint64_t wb = s.wsplit ? 4 : 2;
   p.embed = take((uint64_t)s.V * s.d * wb);
   p.final_norm = take((uint64_t)s.d * 4);
-  p.lm_head = take((uint64_t)s.V * s.d * 2);
+  // FP8 codes in decode order: N rows x ceil(KB / 2) pairs of k blocks x 64 bytes
+  auto fp8_bytes = [](uint64_t N, uint64_t K) { return N * (((K + 31) / 32 + 1) / 2) * 64; };
+  p.lm_head = s.fp8 ? 0 : take((uint64_t)s.V * s.d * 2);  // the output head is only ever streamed by the decode path
   p.lm_head_lo = s.wsplit ? take((uint64_t)s.V * s.d * 2) : 0;
+  p.lm_head8 = s.fp8 ? take(fp8_bytes(s.V, s.d)) : 0;
   p.rope = take((uint64_t)s.max_pos * (s.hd / 2) * 8);
   for (int l = 0; l < s.L; ++l) {
     p.attn_norm.push_back(take((uint64_t)s.d * 4));
@@ -148,6 +154,10 @@ static void make_plan(const www_config* c, Plan& p) {
     p.wgu_lo.push_back(s.wsplit ? take((uint64_t)2 * s.F * s.d * 2) : 0);
     p.wd.push_back(take((uint64_t)s.d * s.Fp * 2));
     p.wd_lo.push_back(s.wsplit ? take((uint64_t)s.d * s.Fp * 2) : 0);
+    p.wqkv8.push_back(s.fp8 ? take(fp8_bytes(s.QKVN, s.d)) : 0);
+    p.wo8.push_back(s.fp8 ? take(fp8_bytes(s.d, s.QD)) : 0);
+    p.wgu8.push_back(s.fp8 ? take(fp8_bytes(2 * (uint64_t)s.F, s.d)) : 0);
+    p.wd8.push_back(s.fp8 ? take(fp8_bytes(s.d, s.Fp)) : 0);
   }
   p.zero_begin = off;
   const uint64_t Mpad = (uint64_t)s.MTmax * 16;
@@ -198,14 +208,19 @@ static void make_plan(const www_config* c, Plan& p) {
   p.total = off;
 }
 
+// bytes of one matrix in the source blob (an FP8 matrix is followed by a 256-byte slot with its scale)
+static uint64_t blob_matrix_bytes(const Dims& s, uint64_t N, uint64_t K) {
+  return s.fp8 ? align256(N * K) + 256 : align256(N * K * (s.wsplit ? 4 : 2));
+}
+
 static uint64_t blob_bytes(const www_config* c) {
   const Dims s = dims_of(c);
-  const uint64_t wb = s.wsplit ? 4 : 2;
-  uint64_t off = align256((uint64_t)s.V * s.d * wb);
+  const uint64_t wb_embed = s.wsplit ? 4 : 2;  // the embedding of an FP8 weight-only model is bf16
+  uint64_t off = align256((uint64_t)s.V * s.d * wb_embed);
   for (int l = 0; l < s.L; ++l)
-    off += align256((uint64_t)s.d * 4) * 2 + align256((uint64_t)s.QKVN * s.d * wb) + align256((uint64_t)s.d * s.QD * wb) +
-           align256((uint64_t)2 * s.F * s.d * wb) + align256((uint64_t)s.d * s.F * wb);
-  off += align256((uint64_t)s.d * 4) + align256((uint64_t)s.V * s.d * wb);
+    off += align256((uint64_t)s.d * 4) * 2 + blob_matrix_bytes(s, s.QKVN, s.d) + blob_matrix_bytes(s, s.d, s.QD) +
+           blob_matrix_bytes(s, 2 * (uint64_t)s.F, s.d) + blob_matrix_bytes(s, s.d, s.F);
+  off += align256((uint64_t)s.d * 4) + blob_matrix_bytes(s, s.V, s.d);
   return off;
 }
 
@@ -244,7 +259,9 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->L = s.L; m->d = s.d; m->Hq = s.Hq; m->Hkv = s.Hkv; m->hd = s.hd; m->G = s.G; m->F = s.F; m->Fp = s.Fp; m->V = s.V;
   m->QKVN = s.QKVN; m->QD = s.QD; m->KD = s.KD; m->max_pos = s.max_pos; m->maxB = s.maxB; m->MTmax = s.MTmax; m->maxT = s.maxT;
   m->wsplit = s.wsplit;
+  m->fp8 = s.fp8;
   m->layers = new LayerW[s.L];
+  memset(m->layers, 0, sizeof(LayerW) * s.L);
   m->graphs = new GraphEntry[MAX_GRAPHS];
   m->n_graphs = 0;
   const char* env = getenv("WWW_NO_GRAPH");
@@ -254,25 +271,42 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
 #define LOAD_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { set_error("%s failed: %s", #x, hipGetErrorString(e_)); return fail(WWW_E_HIP); } } while (0)
 
   uint64_t src = 0;
-  auto pack = [&](int N, int K, int mode, uint64_t hi, uint64_t lo) {
+  std::vector<float*> scale_dst;   // host destinations of the FP8 matrices' scales, in blob order, and
+  std::vector<uint64_t> scale_src; // their byte offsets in the blob
+  // hi (and lo): the fp16 planes of the matrix in the workspace; codes8: its FP8 codes in decode order (FP8 sources).
+  // hi == 0 with an FP8 source: no fp16 copy is made.
+  auto pack = [&](int N, int K, int mode, uint64_t hi, uint64_t lo, uint64_t codes8, float* scale_out) {
     int KB = (K + 31) / 32;
-    int r = launch_pack_matrix(blob + src, dt, N, K, KB, mode, s.hd, (s.Hq + s.Hkv) * s.hd, s.F, (uint16_t*)(ws + hi), s.wsplit ? (uint16_t*)(ws + lo) : nullptr, st);
-    src += align256((uint64_t)N * K * wb);
+    int r = 0;
+    if (!s.fp8 || hi)
+      r = launch_pack_matrix(blob + src, dt, N, K, KB, mode, s.hd, (s.Hq + s.Hkv) * s.hd, s.F, (uint16_t*)(ws + hi), s.wsplit ? (uint16_t*)(ws + lo) : nullptr, st);
+    if (s.fp8) {
+      if (!r) r = launch_pack_fp8(blob + src, N, K, KB, mode, s.hd, (s.Hq + s.Hkv) * s.hd, s.F, (uint8_t*)(ws + codes8), st);
+      scale_dst.push_back(scale_out);
+      scale_src.push_back(src + align256((uint64_t)N * K));
+    } else {
+      *scale_out = 1.f;
+    }
+    src += blob_matrix_bytes(s, N, K);
     return r;
   };
   // embed
   LOAD_TRY(hipMemcpyAsync(ws + p.embed, blob + src, (uint64_t)s.V * s.d * wb, hipMemcpyDeviceToDevice, st));
-  src += align256((uint64_t)s.V * s.d * wb);
+  src += align256((uint64_t)s.V * s.d * wb);  // (an FP8 weight-only model's embedding is bf16: wb = 2)
   for (int l = 0; l < s.L; ++l) {
     LayerW& w = m->layers[l];
     LOAD_TRY(hipMemcpyAsync(ws + p.attn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);
-    if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
-    if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l], p.wqkv8[l], &w.sqkv)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l], p.wo8[l], &w.so)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
     LOAD_TRY(hipMemcpyAsync(ws + p.ffn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);
-    if (pack(2 * s.F, s.d, 2, p.wgu[l], p.wgu_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
-    if (pack(s.d, s.F, 0, p.wd[l], p.wd_lo[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(2 * s.F, s.d, 2, p.wgu[l], p.wgu_lo[l], p.wgu8[l], &w.sgu)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.F, 0, p.wd[l], p.wd_lo[l], p.wd8[l], &w.sd)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (s.fp8) {
+      w.wqkv8 = (const uint8_t*)(ws + p.wqkv8[l]); w.wo8 = (const uint8_t*)(ws + p.wo8[l]);
+      w.wgu8 = (const uint8_t*)(ws + p.wgu8[l]); w.wd8 = (const uint8_t*)(ws + p.wd8[l]);
+    }
     w.wqkv = (const uint16_t*)(ws + p.wqkv[l]); w.wo = (const uint16_t*)(ws + p.wo[l]);
     w.wgu = (const uint16_t*)(ws + p.wgu[l]); w.wd = (const uint16_t*)(ws + p.wd[l]);
     w.wqkv_lo = s.wsplit ? (const uint16_t*)(ws + p.wqkv_lo[l]) : nullptr; w.wo_lo = s.wsplit ? (const uint16_t*)(ws + p.wo_lo[l]) : nullptr;
@@ -281,7 +315,9 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   }
   LOAD_TRY(hipMemcpyAsync(ws + p.final_norm, blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
   src += align256((uint64_t)s.d * 4);
-  if (pack(s.V, s.d, 0, p.lm_head, p.lm_head_lo)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+  if (pack(s.V, s.d, 0, p.lm_head, p.lm_head_lo, p.lm_head8, &m->s_lm)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+  for (size_t i = 0; i < scale_dst.size(); ++i)  // the scales travel to the host: they are kernel arguments
+    LOAD_TRY(hipMemcpyAsync(scale_dst[i], blob + scale_src[i], 4, hipMemcpyDeviceToHost, st));
 
   // rotary table: angle = pos * theta^(-2i/hd) evaluated in double, stored as (cos, sin) in fp32
   {
@@ -300,7 +336,8 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
 #undef LOAD_TRY
 
   m->embed = ws + p.embed;
-  m->lm_head = (const uint16_t*)(ws + p.lm_head);
+  m->lm_head = s.fp8 ? nullptr : (const uint16_t*)(ws + p.lm_head);
+  m->lm_head8 = s.fp8 ? (const uint8_t*)(ws + p.lm_head8) : nullptr;
   m->lm_head_lo = s.wsplit ? (const uint16_t*)(ws + p.lm_head_lo) : nullptr;
   m->final_norm = (const float*)(ws + p.final_norm);
   m->rope = (const float2*)(ws + p.rope);

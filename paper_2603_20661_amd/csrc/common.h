@@ -84,6 +84,8 @@ __device__ __forceinline__ int64_t kv_slot(const int32_t* __restrict__ row, int 
 // ------------------------------------------------------------------------------------------------
 struct LayerW {
   const uint16_t *wqkv, *wqkv_lo, *wo, *wo_lo, *wgu, *wgu_lo, *wd, *wd_lo;  // packed fp16 (lo planes only for fp32 sources)
+  const uint8_t *wqkv8, *wo8, *wgu8, *wd8;  // FP8 weight-only models: packed codes for the decode path ...
+  float sqkv, so, sgu, sd;                  // ... and the matrices' scales (1 otherwise)
   const float *attn_norm, *ffn_norm;
 };
 
@@ -98,6 +100,9 @@ struct www_model {
   www_config cfg;
   int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, max_pos, maxB, MTmax, maxT;
   bool wsplit;
+  bool fp8;  // FP8 weight-only source
+  const uint8_t* lm_head8;
+  float s_lm;
   // weights (inside the workspace)
   LayerW* layers;  // host array
   const void* embed;  // [V][d] in the source dtype
@@ -153,6 +158,7 @@ void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in f
 
 // host-side launchers (decode.hip / prefill.hip / pack.hip)
 void set_error(const char* fmt, ...);
+int launch_pack_fp8(const void* src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F, uint8_t* out, hipStream_t st);
 int decode_attn_resident_waves(int hd, int G);
 int decode_probe_placement(int32_t* scratch_dev, int n, hipStream_t st);
 int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int32_t* table, int batch, float* logits, int32_t* next,

@@ -77,8 +77,9 @@ __global__ __launch_bounds__(256) void embed_pack_kernel(const int32_t* __restri
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
 struct GemmP {
-  const u32x4* W;    // packed weights, 16-byte units
+  const u32x4* W;    // packed weights, 16-byte units (fp16 fragments, or FP8 codes of two k blocks)
   const u32x4* Wlo;  // low-order plane (fp32 sources) or null
+  float wfactor;     // FP8 weights: the matrix's scale, applied to the result
   int NRG, KB;       // row groups of 16, k blocks of 32
   const u32x4* X;    // packed activations
   int MT, M;         // token groups in X, valid tokens
@@ -112,8 +113,23 @@ struct GemmP {
   int V;
 };
 
-template <int MTK, bool WSPLIT, int EPI>
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// 8 FP8 E4M3 codes (two 32-bit words, lowest byte first) -> 8 fp16 values, exact (|value| <= 448); the conversion
+// instruction widens two codes at a time.
+__device__ __forceinline__ f16x8 fp8x8_to_f16x8(uint32_t lo, uint32_t hi) {
+  const f16x2 a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lo, 1.0f, false), b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(lo, 1.0f, true);
+  const f16x2 c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hi, 1.0f, false), d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(hi, 1.0f, true);
+  return __builtin_shufflevector(__builtin_shufflevector(a, b, 0, 1, 2, 3), __builtin_shufflevector(c, d, 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// WMODE: 0 = fp16 weights, 1 = fp16 hi + lo planes (fp32 sources), 2 = FP8 codes, two k blocks per 16-byte unit,
+// widened to fp16 in registers just before the MFMAs (the matrix's scale multiplies the result in the epilogue)
+enum { WMODE_F16 = 0, WMODE_SPLIT = 1, WMODE_FP8 = 2 };
+
+template <int MTK, int WMODE, int EPI>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
+  constexpr bool WSPLIT = WMODE == WMODE_SPLIT, W8 = WMODE == WMODE_FP8;
   constexpr int R = 2, KC = 4, WP = WSPLIT ? 2 : 1;
   constexpr int CHUNK_UNITS = KC * MTK * 128;      // 16-byte units of activations per k chunk
   constexpr int NSTG = CHUNK_UNITS / 256;
@@ -196,7 +212,10 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   // after that barrier
   auto read_scales = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int tb = 0; tb < MTK; ++tb) scale_pre[tb] = p.ssq_in ? s_scale[tb * 16 + (lane & 15)] : 1.f;
+    for (int tb = 0; tb < MTK; ++tb) {
+      scale_pre[tb] = p.ssq_in ? s_scale[tb * 16 + (lane & 15)] : 1.f;
+      if constexpr (W8) scale_pre[tb] *= p.wfactor;
+    }
   };
 
   u32x4 wA[KC][R][WP], wB[KC][R][WP], stg[NSTG];
@@ -204,6 +223,17 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   // Loads past the end of this split's k range are redirected to its last valid block (in bounds) and the
   // matching MFMAs are skipped in compute(): no per-element selects in the streaming loop.
   auto load_w = [&](u32x4(&w)[KC][R][WP], int c) {
+    if constexpr (W8) {
+      // one 16-byte unit carries two k blocks: entries 0 and 2 of the set hold the chunk's two units, 1 and 3 stay unused
+      // (kb_begin is a multiple of 4, so a chunk starts on a pair)
+#pragma unroll
+      for (int kk = 0; kk < KC; kk += 2) {
+        const int pair = min((kb_begin + c * KC + kk) >> 1, (kb_end - 1) >> 1);
+#pragma unroll
+        for (int r = 0; r < R; ++r) w[kk][r][0] = p.W[((int64_t)pair * p.NRG + rgc[r]) * 64 + lane];
+      }
+      return;
+    }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
       const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
@@ -245,12 +275,22 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
       if (kk >= nvalid) break;
       if (kk + 1 < KC) fetch((kk + 1) & 1, kk + 1);
       __builtin_amdgcn_sched_barrier(0);
+      f16x8 a8[R];
+      if constexpr (W8) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const u32x4 raw = w[kk & ~1][r][0];
+          a8[r] = (kk & 1) ? fp8x8_to_f16x8(raw.z, raw.w) : fp8x8_to_f16x8(raw.x, raw.y);
+        }
+      }
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
         const f16x8 bhi = as_f16x8(bq[kk & 1][tb][0]), blo = as_f16x8(bq[kk & 1][tb][1]);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          f16x8 a = as_f16x8(w[kk][r][0]);
+          f16x8 a;
+          if constexpr (W8) a = a8[r];
+          else a = as_f16x8(w[kk][r][0]);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, acc[r][tb], 0, 0, 0);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, acc[r][tb], 0, 0, 0);
           if constexpr (WSPLIT) acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(w[kk][r][1]), bhi, acc[r][tb], 0, 0, 0);
@@ -917,12 +957,15 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.row_tiles = row_tiles;
   p.zbs = zb;
   p.fence_handover = m->handover_fence;
+  if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
   dim3 grid(8 * ((row_tiles + 7) / 8) * p.ksplit * zb), block(256);
-#define LAUNCH(MTK_, WS_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WS_, EPI>), grid, block, 0, st, p);
-  if (m->wsplit) {
-    if (mtk == 1) LAUNCH(1, true) else if (mtk == 2) LAUNCH(2, true) else LAUNCH(4, true)
+#define LAUNCH(MTK_, WM_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WM_, EPI>), grid, block, 0, st, p);
+  if (m->fp8) {
+    if (mtk == 1) LAUNCH(1, WMODE_FP8) else if (mtk == 2) LAUNCH(2, WMODE_FP8) else LAUNCH(4, WMODE_FP8)
+  } else if (m->wsplit) {
+    if (mtk == 1) LAUNCH(1, WMODE_SPLIT) else if (mtk == 2) LAUNCH(2, WMODE_SPLIT) else LAUNCH(4, WMODE_SPLIT)
   } else {
-    if (mtk == 1) LAUNCH(1, false) else if (mtk == 2) LAUNCH(2, false) else LAUNCH(4, false)
+    if (mtk == 1) LAUNCH(1, WMODE_F16) else if (mtk == 2) LAUNCH(2, WMODE_F16) else LAUNCH(4, WMODE_F16)
   }
 #undef LAUNCH
 }
@@ -987,7 +1030,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
     {
       GemmP p = {};
-      p.W = (const u32x4*)w.wqkv; p.Wlo = (const u32x4*)w.wqkv_lo; p.NRG = m->QKVN / 16; p.KB = d / 32;
+      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wqkv8 : (const void*)w.wqkv); p.Wlo = (const u32x4*)w.wqkv_lo; p.wfactor = w.sqkv;
+      p.NRG = m->QKVN / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
@@ -1015,7 +1059,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)w.wo; p.Wlo = (const u32x4*)w.wo_lo; p.NRG = d / 16; p.KB = m->QD / 32;
+      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wo8 : (const void*)w.wo); p.Wlo = (const u32x4*)w.wo_lo; p.wfactor = w.so;
+      p.NRG = d / 16; p.KB = m->QD / 32;
       p.X = (const u32x4*)m->xo; p.M = batch;
       p.h = m->h; p.gain_next = w.ffn_norm; p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.d = d;
       prof_mark(m, PK_OPROJ, st);
@@ -1024,7 +1069,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)w.wgu; p.Wlo = (const u32x4*)w.wgu_lo; p.NRG = 2 * m->F / 16; p.KB = d / 32;
+      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wgu8 : (const void*)w.wgu); p.Wlo = (const u32x4*)w.wgu_lo; p.wfactor = w.sgu;
+      p.NRG = 2 * m->F / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.xa = (uint16_t*)m->xa; p.F = m->F;
@@ -1033,7 +1079,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)w.wd; p.Wlo = (const u32x4*)w.wd_lo; p.NRG = d / 16; p.KB = m->Fp / 32;
+      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wd8 : (const void*)w.wd); p.Wlo = (const u32x4*)w.wd_lo; p.wfactor = w.sd;
+      p.NRG = d / 16; p.KB = m->Fp / 32;
       p.X = (const u32x4*)m->xa; p.M = batch;
       p.h = m->h; p.gain_next = (l + 1 < m->L) ? m->layers[l + 1].attn_norm : m->final_norm;
       p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.d = d;
@@ -1044,7 +1091,8 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
   float* lg = logits ? logits : m->logits_buf;
   {
     GemmP p = {};
-    p.W = (const u32x4*)m->lm_head; p.Wlo = (const u32x4*)m->lm_head_lo; p.NRG = m->V / 16; p.KB = d / 32;
+    p.W = (const u32x4*)(m->fp8 ? (const void*)m->lm_head8 : (const void*)m->lm_head); p.Wlo = (const u32x4*)m->lm_head_lo; p.wfactor = m->s_lm;
+    p.NRG = m->V / 16; p.KB = d / 32;
     p.X = (const u32x4*)m->xq; p.M = batch;
     p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
     p.logits = lg; p.V = m->V;

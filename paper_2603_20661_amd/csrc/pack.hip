@@ -16,6 +16,13 @@ __device__ __forceinline__ int source_row(int p, int mode, int hd, int n_rot_row
   return p;
 }
 
+// Value of an FP8 E4M3 code (OCP: bias 7, subnormals at exponent 0, no infinities), exact in fp16: the seven magnitude
+// bits, moved to fp16's exponent / mantissa position, read as fp16 give the value divided by 2^8 (bias 15 instead of 7).
+__device__ __forceinline__ float e4m3_to_float(uint8_t c) {
+  const uint16_t h = (uint16_t)(((c & 0x80u) << 8) | ((c & 0x7Fu) << 7));
+  return f16_bits_to_float(h) * 256.f;
+}
+
 // one thread = one lane's 8 elements of one fragment
 template <typename SRC>
 __global__ void pack_matrix_kernel(const SRC* __restrict__ src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F,
@@ -38,6 +45,7 @@ __global__ void pack_matrix_kernel(const SRC* __restrict__ src, int N, int K, in
     float x = 0.f;
     if (k < K) {
       if constexpr (sizeof(SRC) == 4) x = (float)src[srow * K + k];
+      else if constexpr (sizeof(SRC) == 1) x = e4m3_to_float(((const uint8_t*)src)[srow * K + k]);  // exact in the hi plane
       else x = bf16_bits_to_float(((const uint16_t*)src)[srow * K + k]);
     }
     split_f16(x, h.s[e], l.s[e]);
@@ -51,12 +59,44 @@ int launch_pack_matrix(const void* src, int src_dtype, int N, int K, int KB, int
   int64_t total = (int64_t)(N / 16) * KB * 64;
   int threads = 256;
   int64_t blocks = (total + threads - 1) / threads;
-  if (src_dtype == (int)WWW_DTYPE_F32)
+  if (src_dtype == (int)WWW_DTYPE_FP8WO)
+    hipLaunchKernelGGL(pack_matrix_kernel<uint8_t>, dim3((unsigned)blocks), dim3(threads), 0, st, (const uint8_t*)src, N, K, KB, mode, hd,
+                       n_rot_rows, F, (uint16_t*)hi, (uint16_t*)nullptr);
+  else if (src_dtype == (int)WWW_DTYPE_F32)
     hipLaunchKernelGGL(pack_matrix_kernel<float>, dim3((unsigned)blocks), dim3(threads), 0, st, (const float*)src, N, K, KB, mode, hd,
                        n_rot_rows, F, (uint16_t*)hi, (uint16_t*)lo);
   else
     hipLaunchKernelGGL(pack_matrix_kernel<uint16_t>, dim3((unsigned)blocks), dim3(threads), 0, st, (const uint16_t*)src, N, K, KB, mode,
                        hd, n_rot_rows, F, (uint16_t*)hi, (uint16_t*)nullptr);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// FP8 codes in the order the decode GEMM streams them: 16-byte unit ((pair of k blocks j, row group rg), lane) holds the
+// lane's 8 codes of k block 2j followed by its 8 codes of k block 2j + 1 (rows and k positions as in the fp16 layout);
+// positions past K, and the second half of a last odd block, are zero codes.
+__global__ void pack_fp8_kernel(const uint8_t* __restrict__ src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F,
+                                uint8_t* __restrict__ out) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int NRG = N / 16, KB2 = (KB + 1) / 2;
+  if (idx >= (int64_t)NRG * KB2 * 64) return;
+  const int lane = (int)(idx & 63);
+  const int64_t unit = idx >> 6;
+  const int rg = (int)(unit % NRG), kb2 = (int)(unit / NRG);
+  const int64_t srow = source_row(rg * 16 + (lane & 15), mode, hd, n_rot_rows, F);
+  union { uint8_t b[16]; uint4 v; } o;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int k0 = (kb2 * 2 + half) * 32 + (lane >> 4) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.b[half * 8 + e] = (k0 + e < K) ? src[srow * K + k0 + e] : (uint8_t)0;
+  }
+  *reinterpret_cast<uint4*>(out + idx * 16) = o.v;
+}
+
+int launch_pack_fp8(const void* src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F, uint8_t* out, hipStream_t st) {
+  const int64_t total = (int64_t)(N / 16) * ((KB + 1) / 2) * 64;
+  hipLaunchKernelGGL(pack_fp8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t*)src, N, K, KB, mode, hd,
+                     n_rot_rows, F, out);
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -95,6 +95,7 @@ enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
 
 struct PGemmP {
   const u32x4* W;  // packed weights
+  float wfactor;   // scale of the matrix (FP8 weight-only sources; 1 otherwise), applied to the result
   int NRG, KB;
   const u32x4* X;  // packed activations
   int T;
@@ -291,7 +292,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     const int t = t_tile + wt * 128 + tb * 32 + (lane & 31);
     tok_ok[tb] = t < p.T;
     tcl[tb] = min(t, p.T - 1);
-    scale[tb] = 1.f;
+    scale[tb] = p.wfactor;
     pos[tb] = 0;
     blk[tb] = 0;
   }
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         for (int c = 0; c < PSSQ / 4; ++c)
 #pragma unroll
           for (int e = 0; e < 4; ++e) ss += (c * 4 + e < p.n_ssq_in) ? sq[u][c][e] : 0.f;
-        scale[half * 2 + u] = rsqrtf(ss * p.inv_dim + p.eps);
+        scale[half * 2 + u] = rsqrtf(ss * p.inv_dim + p.eps) * p.wfactor;
       }
     }
   }
@@ -674,6 +675,7 @@ template <int EPI>
 static void launch_pgemm(PGemmP& p, hipStream_t st) {
   p.n_tt = (p.T + 255) / 256;
   p.n_rt = (p.NRG + 15) / 16;
+  if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
   static bool lds_enabled = false;  // per instantiation: allow 96 KiB of dynamic LDS
   if (!lds_enabled) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, PGEMM_LDS_BYTES);
@@ -721,7 +723,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
+      p.W = (const u32x4*)w.wqkv; p.wfactor = w.sqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
@@ -732,21 +734,21 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     else launch_pattn<64>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wo; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;
+      p.W = (const u32x4*)w.wo; p.wfactor = w.so; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;
       p.hp = m->hp; p.d = d; p.gain_next = w.ffn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
       launch_pgemm<PEPI_RESID>(p, st);
       n_ssq = n_rt_d;
     }
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
+      p.W = (const u32x4*)w.wgu; p.wfactor = w.sgu; p.NRG = 2 * m->F / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.ap = (uint16_t*)m->ap; p.Fp = m->Fp;
       launch_pgemm<PEPI_SWIGLU>(p, st);
     }
     {
       PGemmP p = {};
-      p.W = (const u32x4*)w.wd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
+      p.W = (const u32x4*)w.wd; p.wfactor = w.sd; p.NRG = d / 16; p.KB = m->Fp / 32; p.X = (const u32x4*)m->ap; p.T = T;
       p.hp = m->hp; p.d = d; p.gain_next = m->layers[l + 1].attn_norm; p.xn_out = (uint16_t*)m->xn; p.ssq_out = m->ssq_p;
       launch_pgemm<PEPI_RESID>(p, st);
     }

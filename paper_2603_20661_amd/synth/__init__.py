@@ -293,7 +293,13 @@ class Workload:
 
 
 def workload(name: str) -> Workload:
-    """The synthetic configurations ("tiny", "1b", "8b", "duel_1b", "duel_8b")."""
+    """The synthetic configurations ("tiny", "1b", "8b", "duel_1b", "duel_8b"; "1b-fp8wo" / "8b-fp8wo": the same jobs
+    with the matrices stored as FP8 codes)."""
+    if name.endswith("-fp8wo"):
+        import dataclasses
+        w = workload(name[:-len("-fp8wo")])
+        return Workload(name, dataclasses.replace(w.shape, name=w.shape.name + "-fp8wo", weight_dtype=WDTYPE_FP8WO), w.prompt_lens,
+                        w.prompt_tokens, w.decode_steps)
     if name == "tiny":
         sh = TINY
         lens = np.full(4, 128, dtype=np.int32)

@@ -7,6 +7,14 @@ import numpy as np
 from paper_2603_20661_amd import synth
 
 
+def oracle_view(shape, blob):
+    """What the model oracle is given: the blob itself, or, for an fp8 weight-only model, its decoded fp32 form."""
+    if shape.weight_dtype == synth.WDTYPE_FP8WO:
+        from oracle import quant
+        return quant.dequantize_blob(shape, blob)
+    return shape, blob
+
+
 def gpu_modules():
     import torch
     from paper_2603_20661_amd import binding
@@ -65,6 +73,7 @@ def oracle_replay(shape, blob, prompt, generated):
     (teacher-forced).  Returns logits [1 + len(generated), V]: after the prompt and after each appended token."""
     from oracle import oracle as O
     n = len(prompt) + len(generated)
+    shape, blob = oracle_view(shape, blob)
     m = O.OracleModel(shape, blob, max_seqs=1, max_ctx=n + 1)
     out = []
     lg, _, _ = m.forward(prompt, [len(prompt)], [len(prompt)], seq_ids=[0])
@@ -81,6 +90,7 @@ def oracle_job(shape, blob, lens, toks, steps, table, num_blocks, chunk=None):
     Returns logits [steps+1, B, V] and the greedy tokens [steps+1, B]."""
     from oracle import oracle as O
     Bn = len(lens)
+    shape, blob = oracle_view(shape, blob)
     m = O.OracleModel(shape, blob, max_seqs=0, max_ctx=0, num_blocks=num_blocks)
     lens = np.asarray(lens, np.int32)
     starts = np.concatenate([[0], np.cumsum(lens)[:-1]])

@@ -159,6 +159,31 @@ def test_full_width_layers_at_bench_batch(shape, batch):
     check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
 
 
+# ------------------------------------------------------------------ fp8 weight-only models
+MID128_FP8 = dataclasses.replace(MID128, name="mid128fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=24)
+MID64_FP8 = dataclasses.replace(MID64, name="mid64fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=25)
+WIDE8B_FP8 = dataclasses.replace(WIDE8B, name="wide8bfp8", weight_dtype=synth.WDTYPE_FP8WO, seed=33)
+WIDE1B_FP8 = dataclasses.replace(WIDE1B, name="wide1bfp8", weight_dtype=synth.WDTYPE_FP8WO, seed=34)
+
+
+@pytest.mark.parametrize("shape,lens,steps,chunk", [
+    (MID64_FP8, [1, 17, 150, 40, 9], 6, None),            # token group of 16, ragged prompts
+    (MID128_FP8, [200, 31, 64, 5, 90, 33, 16, 1] * 3, 5, None),   # 24 sequences: two token groups
+    (MID128_FP8, [130, 47, 300], 4, 37),                   # chunked prefill
+])
+def test_fp8_weight_only_models(shape, lens, steps, chunk):
+    """Weights stored as E4M3 codes with one scale per matrix: the decode path widens the codes in registers, the
+    prefill path reads an fp16 copy; the oracle runs the decoded fp32 model.  Same bars as everywhere."""
+    check(run_job(shape, lens, steps, seed=120 + len(lens), chunk=chunk, gain_std=0.1), f"{shape.name} lens={len(lens)} chunk={chunk}")
+
+
+@pytest.mark.parametrize("shape,batch", [(WIDE8B_FP8, 64), (WIDE1B_FP8, 32), (WIDE8B_FP8, 70)])
+def test_fp8_weight_only_full_width_layers(shape, batch):
+    lens = 1 + synth.uniform_i32(batch, 13, batch, 40)
+    lens[0], lens[1] = 1, 16
+    check(run_job(shape, lens, 3, seed=140 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+
+
 @pytest.mark.parametrize("fence", ["0", "1"])
 def test_repeated_calls_are_bitwise_identical(fence, monkeypatch):
     """GPU vs GPU: the same decode step and the same prefill, issued again and again on one model, give the same bits.
