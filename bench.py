@@ -48,29 +48,41 @@ CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
 # Counter units per launch, averaged over the 256 launches of those runs; scale = bytes per unit / 1024, from what the
 # same counter read for the calibration copy above (131 088.1 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
 # of WRITE_SIZE for 262 144 KiB written); algorithmic bytes of those same launches for rescaling to another context.
-# Valid only for the kernel sources it was taken with: reported as null when their hash differs.
+# Valid only for the kernels it was taken with: the hash covers the text of the attention plan / attention / merge kernels
+# in decode.hip and of the layout helpers in common.h; the reading is reported as null when that text has changed.
 TRAFFIC = {
     "workload": "8b", "kernel": "decode_attention",
     "fetch_units": 163132.1 + 1674.0, "write_units": 3112.7 + 1024.0,
     "fetch_scale": 262144.0 / 131088.1, "write_scale": 1.0,
     "algorithmic_bytes_of_measured_launches": 80383 * 4096,
-    "sources": ("paper_2603_20661_amd/csrc/decode.hip", "paper_2603_20661_amd/csrc/common.h"),
-    "sha256": "9523f23b425160d3849b45e21fada3349d932ad1485bcbebb73a1ea98d19c35a",
+    "sources": (("paper_2603_20661_amd/csrc/decode.hip", "// Plan of the decode attention", "void argmax_take("),
+                ("paper_2603_20661_amd/csrc/common.h", "inline int64_t packed_w_elems(", "struct LayerW {")),
+    "sha256": "2aa824a20d2877c2f3fa35b41161f401fefd82776e851b17b6cbdca54340bc19",
 }
+
+
+def kernel_text_hash():
+    """sha256 over the source text of the measured kernels (from a start marker up to an end marker in each file)"""
+    import hashlib
+    h = hashlib.sha256()
+    for f, start, end in TRAFFIC["sources"]:
+        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), f), "r") as fh:
+            text = fh.read()
+        a = text.index(start)
+        h.update(text[a:text.index(end, a)].encode())
+    return h.hexdigest()
 
 
 def measured_traffic(workload, kernel, algorithmic_bytes_per_launch):
     """HBM bytes per launch of `kernel` from the stored counter readings, rescaled linearly to this launch's algorithmic
     bytes (attention traffic is proportional to the context); None if there is no reading for this workload / kernel or the
     kernel sources have changed since it was taken."""
-    import hashlib
     if workload != TRAFFIC["workload"] or kernel != TRAFFIC["kernel"]:
         return None
-    h = hashlib.sha256()
-    for f in TRAFFIC["sources"]:
-        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), f), "rb") as fh:
-            h.update(fh.read())
-    if h.hexdigest() != TRAFFIC["sha256"]:
+    try:
+        if kernel_text_hash() != TRAFFIC["sha256"]:
+            return None
+    except (OSError, ValueError):
         return None
     measured = (TRAFFIC["fetch_units"] * TRAFFIC["fetch_scale"] + TRAFFIC["write_units"] * TRAFFIC["write_scale"]) * 1024.0
     return int(round(measured * algorithmic_bytes_per_launch / TRAFFIC["algorithmic_bytes_of_measured_launches"]))
