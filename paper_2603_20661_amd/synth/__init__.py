@@ -26,6 +26,9 @@ _lib = None
 WDTYPE_F32 = 0
 WDTYPE_BF16 = 1
 WDTYPE_FP8WO = 2   # matrices as FP8 E4M3 codes with one fp32 scale per matrix; embedding bf16
+WDTYPE_INT4WO_128 = 3   # matrices as 4-bit codes with one bf16 scale per 128 consecutive weights of a row; embedding bf16
+WDTYPE_INT4WO_32 = 4    # the same with groups of 32
+INT4_GROUP = {WDTYPE_INT4WO_128: 128, WDTYPE_INT4WO_32: 32}
 KV_BLOCK = 16
 ALIGN = 256  # every tensor of the weight blob starts on a 256-byte boundary
 
@@ -51,6 +54,8 @@ def _load():
         lib.wwwsynth_uniform_i32.argtypes = [u64, u64, u64, u64, ctypes.c_uint32, vp]
         lib.wwwsynth_encode_e4m3.argtypes = [vp, u64, dbl, vp]
         lib.wwwsynth_encode_e4m3.restype = None
+        lib.wwwsynth_encode_int4.argtypes = [vp, u64, u64, u64, vp, vp]
+        lib.wwwsynth_encode_int4.restype = None
         lib.wwwsynth_mix.argtypes = [u64]
         lib.wwwsynth_mix.restype = u64
         for f in (lib.wwwsynth_normal_f32, lib.wwwsynth_normal_bf16, lib.wwwsynth_words, lib.wwwsynth_uniform_i32):
@@ -157,14 +162,22 @@ def blob_layout(shape: ModelShape):
     def add(name, rows, cols, dt):
         nonlocal off
         entries.append((name, off, rows, cols, dt))
-        nbytes = rows * cols * {WDTYPE_F32: 4, WDTYPE_BF16: 2, WDTYPE_FP8WO: 1}[dt]
+        if dt in INT4_GROUP:
+            assert cols % INT4_GROUP[dt] == 0, f"{name}: {cols} columns are not a multiple of the group size"
+            nbytes = rows * cols // 2
+        else:
+            nbytes = rows * cols * {WDTYPE_F32: 4, WDTYPE_BF16: 2, WDTYPE_FP8WO: 1}[dt]
         off += (nbytes + ALIGN - 1) // ALIGN * ALIGN
         if dt == WDTYPE_FP8WO:      # the matrix's scale follows it in a slot of its own
             entries.append((name + ".scale", off, 1, 1, WDTYPE_F32))
             off += ALIGN
+        if dt in INT4_GROUP:        # bf16 scales [rows][cols / group] follow the codes
+            ng = cols // INT4_GROUP[dt]
+            entries.append((name + ".scale", off, rows, ng, WDTYPE_BF16))
+            off += (rows * ng * 2 + ALIGN - 1) // ALIGN * ALIGN
 
     wd = shape.weight_dtype
-    add("embed", V, d, WDTYPE_BF16 if wd == WDTYPE_FP8WO else wd)
+    add("embed", V, d, WDTYPE_BF16 if wd in (WDTYPE_FP8WO, WDTYPE_INT4WO_128, WDTYPE_INT4WO_32) else wd)
     for l in range(shape.n_layers):
         add(f"l{l}.attn_norm", 1, d, WDTYPE_F32)
         add(f"l{l}.wqkv", shape.qkv_rows, d, wd)
@@ -200,6 +213,13 @@ def make_blob(shape: ModelShape, std: float = 0.02, gain_std: float = 0.0, seed=
             blob[soff:soff + 4].view(np.float32)[0] = scale
             del w
             continue
+        if dt in INT4_GROUP and not name.endswith(".scale"):
+            w = normal_f32(seed, t, n, std=std)
+            soff, ng = entries[t + 1][1], cols // INT4_GROUP[dt]
+            _load().wwwsynth_encode_int4(w.ctypes.data, rows, cols, INT4_GROUP[dt], blob[off:off + n // 2].ctypes.data,
+                                         blob[soff:soff + rows * ng * 2].ctypes.data)
+            del w
+            continue
         if name.endswith("norm"):
             view = blob[off:off + 4 * n].view(np.float32)
             if gain_std > 0:
@@ -219,8 +239,8 @@ def blob_tensor(shape: ModelShape, blob: np.ndarray, name: str) -> np.ndarray:
     for (nm, off, rows, cols, dt) in entries:
         if nm == name:
             n = rows * cols
-            if dt == WDTYPE_FP8WO:
-                raise ValueError("fp8 matrices are not decoded here (the generators hold none of the method's arithmetic)")
+            if dt == WDTYPE_FP8WO or dt in INT4_GROUP:
+                raise ValueError("quantised matrices are not decoded here (the generators hold none of the method's arithmetic)")
             if dt == WDTYPE_F32:
                 a = blob[off:off + 4 * n].view(np.float32).copy()
             else:
@@ -294,12 +314,13 @@ class Workload:
 
 def workload(name: str) -> Workload:
     """The synthetic configurations ("tiny", "1b", "8b", "duel_1b", "duel_8b"; "1b-fp8wo" / "8b-fp8wo": the same jobs
-    with the matrices stored as FP8 codes)."""
-    if name.endswith("-fp8wo"):
-        import dataclasses
-        w = workload(name[:-len("-fp8wo")])
-        return Workload(name, dataclasses.replace(w.shape, name=w.shape.name + "-fp8wo", weight_dtype=WDTYPE_FP8WO), w.prompt_lens,
-                        w.prompt_tokens, w.decode_steps)
+    with the matrices stored as FP8 codes; "-int4wo128" / "-int4wo32": as 4-bit codes with group-wise scales)."""
+    for suffix, dt in (("-fp8wo", WDTYPE_FP8WO), ("-int4wo128", WDTYPE_INT4WO_128), ("-int4wo32", WDTYPE_INT4WO_32)):
+        if name.endswith(suffix):
+            import dataclasses
+            w = workload(name[:-len(suffix)])
+            return Workload(name, dataclasses.replace(w.shape, name=w.shape.name + suffix, weight_dtype=dt), w.prompt_lens,
+                            w.prompt_tokens, w.decode_steps)
     if name == "tiny":
         sh = TINY
         lens = np.full(4, 128, dtype=np.int32)

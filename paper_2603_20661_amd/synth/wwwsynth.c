@@ -80,6 +80,31 @@ void wwwsynth_encode_e4m3(const float* src, uint64_t n, double inv_scale, uint8_
   for (int64_t i = 0; i < (int64_t)n; ++i) out[i] = f32_to_e4m3(src[i] * f);
 }
 
+/* Group-wise 4-bit codes of a [rows][cols] fp32 matrix (input recipe of the int4 weight-only configurations): for
+ * every run of `group` consecutive elements of a row, scale = bf16(max|w| / 7) (1 if the run is all zero),
+ * code = clamp(rint(w / scale) + 8, 0, 15); two codes per byte, the element with the even column in the low nibble.
+ * codes: rows * cols / 2 bytes; scales: rows * (cols / group) bf16 patterns, row-major. */
+void wwwsynth_encode_int4(const float* src, uint64_t rows, uint64_t cols, uint64_t group, uint8_t* codes, uint16_t* scales) {
+  const uint64_t ng = cols / group;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < (int64_t)rows; ++r)
+    for (uint64_t g = 0; g < ng; ++g) {
+      const float* w = src + (uint64_t)r * cols + g * group;
+      float amax = 0.f;
+      for (uint64_t i = 0; i < group; ++i) amax = fmaxf(amax, fabsf(w[i]));
+      uint16_t sb = amax > 0.f ? f32_to_bf16_bits(amax / 7.f) : (uint16_t)0x3F80;
+      union { uint32_t u; float f; } sv; sv.u = (uint32_t)sb << 16;
+      scales[(uint64_t)r * ng + g] = sb;
+      uint8_t* out = codes + ((uint64_t)r * cols + g * group) / 2;
+      for (uint64_t i = 0; i < group; i += 2) {
+        int q0 = (int)rintf(w[i] / sv.f) + 8, q1 = (int)rintf(w[i + 1] / sv.f) + 8;
+        q0 = q0 < 0 ? 0 : q0 > 15 ? 15 : q0;
+        q1 = q1 < 0 ? 0 : q1 > 15 ? 15 : q1;
+        out[i / 2] = (uint8_t)(q0 | (q1 << 4));
+      }
+    }
+}
+
 /* the bare mixing function, exported so that tests can check it against SplitMix64's published outputs */
 uint64_t wwwsynth_mix(uint64_t z) { return mix(z); }
 

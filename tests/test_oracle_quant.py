@@ -69,6 +69,37 @@ def test_blob_decoder_matches_tensor_by_tensor_decode():
     assert np.array_equal(emb, synth.bf16_bits_to_f32(blob[:2 * T8.vocab * T8.d_model].view(np.uint16)).reshape(T8.vocab, T8.d_model))
 
 
+T4 = {g: synth.ModelShape(f"t4g{g}", 2, 128, 4, 2, 32, 256, 48, 1e-5, 1e4, dt, seed=52)
+      for g, dt in ((128, synth.WDTYPE_INT4WO_128), (32, synth.WDTYPE_INT4WO_32))}
+
+
+@pytest.mark.parametrize("group", [128, 32])
+def test_int4_blob_decoder_against_the_definition_and_the_recipe(group):
+    """Decoded weights are (code - 8) * scale element by element (checked through an independent unpacking), every group's
+    largest weight lands on code 1 or 15, and the rounding error of a weight is at most half a step of its group."""
+    sh = T4[group]
+    blob = synth.make_blob(sh)
+    entries, total = synth.blob_layout(sh)
+    assert total == blob.size
+    shape32, blob32 = Q.dequantize_blob(sh, blob)
+    by_name = {e[0]: (t, e) for t, e in enumerate(entries)}
+    for name in ("l0.wqkv", "l1.wd", "lm_head"):
+        t, (_, off, rows, cols, dt) = by_name[name]
+        _, (_, soff, srows, ng, sdt) = by_name[name + ".scale"]
+        assert (srows, ng, sdt) == (rows, cols // group, synth.WDTYPE_BF16)
+        got = synth.blob_tensor(shape32, blob32, name)
+        scales = synth.bf16_bits_to_f32(blob[soff:soff + rows * ng * 2].view(np.uint16)).reshape(rows, ng)
+        for r, k in ((0, 0), (0, 1), (3, group - 1), (rows - 1, cols - 1), (5, group % cols), (7, cols // 2 + 3)):
+            byte = int(blob[off + (r * cols + k) // 2])
+            code = (byte >> 4) if k % 2 else (byte & 0xF)
+            assert got[r, k] == np.float32((code - 8) * float(scales[r, k // group]))
+        w = synth.normal_f32(sh.seed, t, rows * cols, std=0.02).reshape(rows, cols)     # what the codes were made from
+        step = np.repeat(scales, group, axis=1)
+        assert (np.abs(got - w) <= 0.5 * step * (1 + 1e-6)).all()
+        amax_code = np.abs(got / step).reshape(rows, ng, group).max(axis=2)
+        assert (amax_code == 7).all()
+
+
 def test_quantised_model_runs_through_the_model_oracle_and_stays_close_to_the_unquantised_one():
     """Sanity of the whole chain: the decoded blob is a valid fp32 model whose logits differ from those of the fp32
     weights it was rounded from by a few per cent of their spread (E4M3 keeps 3 mantissa bits)."""
