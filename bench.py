@@ -24,8 +24,9 @@ Two composite workloads print the same kind of line with their own phases:
 
   --workload 8b-fp8wo / 1b-fp8wo   the 8B / 1B jobs with the matrices stored as FP8 E4M3 codes (weight-only; arithmetic
                      and activations unchanged); rooflines count one byte per streamed weight
+  --workload 8b-int4wo128 / 8b-int4wo32 / 1b-...   the same with 4-bit codes and a bf16 scale per group of 128 / 32
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed|8b-fp8wo|1b-fp8wo]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed|8b-fp8wo|8b-int4wo128|...]
 """
 from __future__ import annotations
 
@@ -99,7 +100,8 @@ def decode_bytes_per_class(shape, ctx_lens, batch):
     d, F, V, L = shape.d_model, shape.ffn_dim, shape.vocab, shape.n_layers
     QD, KD = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
     kv_tok_layer = 2 * KD * 2
-    wb = 1 if shape.weight_dtype == 2 else 2      # bytes per streamed weight: FP8 codes, else 16-bit
+    # bytes per streamed weight: 16-bit, FP8 codes, or 4-bit codes plus a bf16 scale per group of 128 / 32
+    wb = {0: 2, 1: 2, 2: 1, 3: 0.5 + 2 / 128, 4: 0.5 + 2 / 32}[shape.weight_dtype]
     return {
         "embed": batch * d * 2,
         "qkv_gemm": (QD + 2 * KD) * d * wb + batch * kv_tok_layer,     # weights + this token's K/V write
@@ -115,7 +117,7 @@ def decode_bytes_per_class(shape, ctx_lens, batch):
 
 def decode_step_bytes(shape, ctx_lens, batch):
     per, mult = decode_bytes_per_class(shape, ctx_lens, batch)
-    return sum(per[k] * mult[k] for k in per if k != "argmax")
+    return float(sum(per[k] * mult[k] for k in per if k != "argmax"))
 
 
 def prefill_call_flops(shape, q_lens, seq_lens):
@@ -421,7 +423,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed", "1b-fp8wo", "8b-fp8wo"])
+    ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed", "1b-fp8wo", "8b-fp8wo", "1b-int4wo128", "8b-int4wo128",
+                                                          "1b-int4wo32", "8b-int4wo32"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -540,7 +543,7 @@ def main():
                     "algorithmic_bytes_per_launch": int(per_bytes[dom]), "avg_launch_ms": kernels[dom]["avg_ms"]}
 
     cpu = None
-    if not args.no_cpu_baseline and shape.weight_dtype != 2:   # (the fp8 weight-only workloads are not the bench line)
+    if not args.no_cpu_baseline and shape.weight_dtype < 2:   # (the weight-only quantised workloads are not the bench line)
         cpu = cpu_baseline(shape, blob, lens, nsteps)
 
     out = {

@@ -68,6 +68,13 @@ extern "C" {
                               256-byte slot; weight = value(code) * scale.  The embedding stays bf16, gains fp32, and
                               activations and arithmetic are those of the unquantised model.  The decode path streams the
                               codes (half the bytes) and widens them to fp16 in registers; prefill uses an fp16 copy. */
+#define WWW_DTYPE_INT4WO_128 3u /* weight-only int4, groups of 128 ("int4wo-128" of the same experiment; format again this
+                              library's reading): every projection matrix and the output head as 4-bit codes c in 0..15,
+                              two per byte (even column in the low nibble), row-major, followed, on the next 256-byte
+                              boundary, by bf16 scales [rows][cols / 128]; weight = (c - 8) * scale of its run of 128
+                              consecutive columns.  d_model, n_q_heads * head_dim and ffn_dim must be multiples of 128.
+                              Everything else as for WWW_DTYPE_FP8WO. */
+#define WWW_DTYPE_INT4WO_32 4u  /* the same with runs of 32 columns ("int4wo-32"); the three sizes must be multiples of 32 */
 
 typedef struct www_model www_model; /* opaque handle */
 

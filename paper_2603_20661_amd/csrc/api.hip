@@ -73,13 +73,19 @@ static int check_config(const www_config* c) {
   else if (c->n_q_heads % c->n_kv_heads) why = "n_q_heads must be a multiple of n_kv_heads";
   else if (int g = c->n_q_heads / c->n_kv_heads; g != 1 && g != 2 && g != 4 && g != 8) why = "query heads per kv head must be 1, 2, 4 or 8";
   else if (c->kv_block_size != KV_BS) why = "kv_block_size must be 16";
-  else if (c->weight_dtype > 2) why = "weight_dtype must be 0 (fp32), 1 (bf16) or 2 (FP8 weight-only)";
+  else if (c->weight_dtype > 4) why = "weight_dtype must be 0 (fp32), 1 (bf16), 2 (FP8 weight-only), 3 or 4 (int4 weight-only, groups of 128 / 32)";
+
   else if (c->max_batch == 0 || c->max_batch > 1024) why = "max_batch must be in 1..1024";
   else if (c->max_blocks_per_seq == 0 || c->num_kv_blocks == 0) why = "empty KV pool";
   else if (c->num_kv_blocks > 0x7fffffffull) why = "num_kv_blocks must fit int32";
   else if (c->max_prefill_tokens == 0) why = "max_prefill_tokens must be positive";
   else if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) why = "bad rms_eps / rope_theta";
   else if (c->reserved != 0) why = "reserved must be 0";
+  if (!why && c->weight_dtype >= WWW_DTYPE_INT4WO_128) {
+    const uint32_t g = c->weight_dtype == WWW_DTYPE_INT4WO_128 ? 128u : 32u;
+    if (c->d_model % g || (c->n_q_heads * c->head_dim) % g || c->ffn_dim % g)
+      why = "int4 weight-only: d_model, n_q_heads * head_dim and ffn_dim must be multiples of the group size";
+  }
   if (why) { set_error("unsupported configuration: %s", why); return WWW_E_BAD_CONFIG; }
   return WWW_OK;
 }
@@ -105,8 +111,9 @@ struct Plan {
   uint64_t total;
   uint64_t embed, final_norm, lm_head, lm_head_lo, rope;
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
-  std::vector<uint64_t> wqkv8, wo8, wgu8, wd8;  // FP8 weight-only models: packed codes for the decode path
-  uint64_t lm_head8;
+  std::vector<uint64_t> wqkv8, wo8, wgu8, wd8;  // weight-only quantised models: packed codes for the decode path
+  std::vector<uint64_t> gqkv, go, ggu, gd;      // int4: group scales for the decode path
+  uint64_t lm_head8, g_lm;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
   uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_hdr, attn_start, attn_pref;
   uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
@@ -116,6 +123,7 @@ struct Plan {
 struct Dims {
   int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, maxB, MTmax, maxT, max_pos;
   bool wsplit, fp8;
+  int int4_group;  // 0: not an int4 source
 };
 
 static Dims dims_of(const www_config* c) {
@@ -127,6 +135,7 @@ static Dims dims_of(const www_config* c) {
   s.max_pos = c->max_blocks_per_seq * KV_BS;
   s.wsplit = c->weight_dtype == WWW_DTYPE_F32;
   s.fp8 = c->weight_dtype == WWW_DTYPE_FP8WO;
+  s.int4_group = c->weight_dtype == WWW_DTYPE_INT4WO_128 ? 128 : c->weight_dtype == WWW_DTYPE_INT4WO_32 ? 32 : 0;
   return s;
 }
 
@@ -138,10 +147,17 @@ static void make_plan(const www_config* c, Plan& p) {
   p.embed = take((uint64_t)s.V * s.d * wb);
   p.final_norm = take((uint64_t)s.d * 4);
   // FP8 codes in decode order: N rows x ceil(KB / 2) pairs of k blocks x 64 bytes
-  auto fp8_bytes = [](uint64_t N, uint64_t K) { return N * (((K + 31) / 32 + 1) / 2) * 64; };
-  p.lm_head = s.fp8 ? 0 : take((uint64_t)s.V * s.d * 2);  // the output head is only ever streamed by the decode path
+  // int4 codes in decode order: N rows x ceil(KB / 4) chunks x 64 bytes; their scales: 8 bytes per row and chunk
+  const bool quant = s.fp8 || s.int4_group;
+  auto fp8_bytes = [&](uint64_t N, uint64_t K) {
+    const uint64_t KB = (K + 31) / 32;
+    return s.int4_group ? N * ((KB + 3) / 4) * 64 : N * ((KB + 1) / 2) * 64;
+  };
+  auto gscale_bytes = [&](uint64_t N, uint64_t K) { return N * (((K + 31) / 32 + 3) / 4) * 8; };
+  p.lm_head = quant ? 0 : take((uint64_t)s.V * s.d * 2);  // the output head is only ever streamed by the decode path
   p.lm_head_lo = s.wsplit ? take((uint64_t)s.V * s.d * 2) : 0;
-  p.lm_head8 = s.fp8 ? take(fp8_bytes(s.V, s.d)) : 0;
+  p.lm_head8 = quant ? take(fp8_bytes(s.V, s.d)) : 0;
+  p.g_lm = s.int4_group ? take(gscale_bytes(s.V, s.d)) : 0;
   p.rope = take((uint64_t)s.max_pos * (s.hd / 2) * 8);
   for (int l = 0; l < s.L; ++l) {
     p.attn_norm.push_back(take((uint64_t)s.d * 4));
@@ -154,10 +170,14 @@ static void make_plan(const www_config* c, Plan& p) {
     p.wgu_lo.push_back(s.wsplit ? take((uint64_t)2 * s.F * s.d * 2) : 0);
     p.wd.push_back(take((uint64_t)s.d * s.Fp * 2));
     p.wd_lo.push_back(s.wsplit ? take((uint64_t)s.d * s.Fp * 2) : 0);
-    p.wqkv8.push_back(s.fp8 ? take(fp8_bytes(s.QKVN, s.d)) : 0);
-    p.wo8.push_back(s.fp8 ? take(fp8_bytes(s.d, s.QD)) : 0);
-    p.wgu8.push_back(s.fp8 ? take(fp8_bytes(2 * (uint64_t)s.F, s.d)) : 0);
-    p.wd8.push_back(s.fp8 ? take(fp8_bytes(s.d, s.Fp)) : 0);
+    p.wqkv8.push_back(quant ? take(fp8_bytes(s.QKVN, s.d)) : 0);
+    p.wo8.push_back(quant ? take(fp8_bytes(s.d, s.QD)) : 0);
+    p.wgu8.push_back(quant ? take(fp8_bytes(2 * (uint64_t)s.F, s.d)) : 0);
+    p.wd8.push_back(quant ? take(fp8_bytes(s.d, s.Fp)) : 0);
+    p.gqkv.push_back(s.int4_group ? take(gscale_bytes(s.QKVN, s.d)) : 0);
+    p.go.push_back(s.int4_group ? take(gscale_bytes(s.d, s.QD)) : 0);
+    p.ggu.push_back(s.int4_group ? take(gscale_bytes(2 * (uint64_t)s.F, s.d)) : 0);
+    p.gd.push_back(s.int4_group ? take(gscale_bytes(s.d, s.Fp)) : 0);
   }
   p.zero_begin = off;
   const uint64_t Mpad = (uint64_t)s.MTmax * 16;
@@ -210,6 +230,7 @@ static void make_plan(const www_config* c, Plan& p) {
 
 // bytes of one matrix in the source blob (an FP8 matrix is followed by a 256-byte slot with its scale)
 static uint64_t blob_matrix_bytes(const Dims& s, uint64_t N, uint64_t K) {
+  if (s.int4_group) return align256(N * K / 2) + align256(N * (K / s.int4_group) * 2);  // codes, then bf16 group scales
   return s.fp8 ? align256(N * K) + 256 : align256(N * K * (s.wsplit ? 4 : 2));
 }
 
@@ -260,6 +281,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->QKVN = s.QKVN; m->QD = s.QD; m->KD = s.KD; m->max_pos = s.max_pos; m->maxB = s.maxB; m->MTmax = s.MTmax; m->maxT = s.maxT;
   m->wsplit = s.wsplit;
   m->fp8 = s.fp8;
+  m->int4_group = s.int4_group;
   m->layers = new LayerW[s.L];
   memset(m->layers, 0, sizeof(LayerW) * s.L);
   m->graphs = new GraphEntry[MAX_GRAPHS];
@@ -275,9 +297,16 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   std::vector<uint64_t> scale_src; // their byte offsets in the blob
   // hi (and lo): the fp16 planes of the matrix in the workspace; codes8: its FP8 codes in decode order (FP8 sources).
   // hi == 0 with an FP8 source: no fp16 copy is made.
-  auto pack = [&](int N, int K, int mode, uint64_t hi, uint64_t lo, uint64_t codes8, float* scale_out) {
+  auto pack = [&](int N, int K, int mode, uint64_t hi, uint64_t lo, uint64_t codes8, float* scale_out, uint64_t gscales) {
     int KB = (K + 31) / 32;
     int r = 0;
+    if (s.int4_group) {
+      *scale_out = 1.f;
+      r = launch_pack_int4(blob + src, blob + src + align256((uint64_t)N * K / 2), N, K, KB, s.int4_group, mode, s.hd, (s.Hq + s.Hkv) * s.hd,
+                           s.F, hi ? (uint16_t*)(ws + hi) : nullptr, (uint8_t*)(ws + codes8), ws + gscales, st);
+      src += blob_matrix_bytes(s, N, K);
+      return r;
+    }
     if (!s.fp8 || hi)
       r = launch_pack_matrix(blob + src, dt, N, K, KB, mode, s.hd, (s.Hq + s.Hkv) * s.hd, s.F, (uint16_t*)(ws + hi), s.wsplit ? (uint16_t*)(ws + lo) : nullptr, st);
     if (s.fp8) {
@@ -297,16 +326,17 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
     LayerW& w = m->layers[l];
     LOAD_TRY(hipMemcpyAsync(ws + p.attn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);
-    if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l], p.wqkv8[l], &w.sqkv)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
-    if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l], p.wo8[l], &w.so)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l], p.wqkv8[l], &w.sqkv, p.gqkv[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l], p.wo8[l], &w.so, p.go[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
     LOAD_TRY(hipMemcpyAsync(ws + p.ffn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);
-    if (pack(2 * s.F, s.d, 2, p.wgu[l], p.wgu_lo[l], p.wgu8[l], &w.sgu)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
-    if (pack(s.d, s.F, 0, p.wd[l], p.wd_lo[l], p.wd8[l], &w.sd)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
-    if (s.fp8) {
+    if (pack(2 * s.F, s.d, 2, p.wgu[l], p.wgu_lo[l], p.wgu8[l], &w.sgu, p.ggu[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (pack(s.d, s.F, 0, p.wd[l], p.wd_lo[l], p.wd8[l], &w.sd, p.gd[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (s.fp8 || s.int4_group) {
       w.wqkv8 = (const uint8_t*)(ws + p.wqkv8[l]); w.wo8 = (const uint8_t*)(ws + p.wo8[l]);
       w.wgu8 = (const uint8_t*)(ws + p.wgu8[l]); w.wd8 = (const uint8_t*)(ws + p.wd8[l]);
     }
+    if (s.int4_group) { w.gqkv = ws + p.gqkv[l]; w.go = ws + p.go[l]; w.ggu = ws + p.ggu[l]; w.gd = ws + p.gd[l]; }
     w.wqkv = (const uint16_t*)(ws + p.wqkv[l]); w.wo = (const uint16_t*)(ws + p.wo[l]);
     w.wgu = (const uint16_t*)(ws + p.wgu[l]); w.wd = (const uint16_t*)(ws + p.wd[l]);
     w.wqkv_lo = s.wsplit ? (const uint16_t*)(ws + p.wqkv_lo[l]) : nullptr; w.wo_lo = s.wsplit ? (const uint16_t*)(ws + p.wo_lo[l]) : nullptr;
@@ -315,7 +345,7 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   }
   LOAD_TRY(hipMemcpyAsync(ws + p.final_norm, blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
   src += align256((uint64_t)s.d * 4);
-  if (pack(s.V, s.d, 0, p.lm_head, p.lm_head_lo, p.lm_head8, &m->s_lm)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+  if (pack(s.V, s.d, 0, p.lm_head, p.lm_head_lo, p.lm_head8, &m->s_lm, p.g_lm)) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
   for (size_t i = 0; i < scale_dst.size(); ++i)  // the scales travel to the host: they are kernel arguments
     LOAD_TRY(hipMemcpyAsync(scale_dst[i], blob + scale_src[i], 4, hipMemcpyDeviceToHost, st));
 
@@ -336,8 +366,9 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
 #undef LOAD_TRY
 
   m->embed = ws + p.embed;
-  m->lm_head = s.fp8 ? nullptr : (const uint16_t*)(ws + p.lm_head);
-  m->lm_head8 = s.fp8 ? (const uint8_t*)(ws + p.lm_head8) : nullptr;
+  m->lm_head = (s.fp8 || s.int4_group) ? nullptr : (const uint16_t*)(ws + p.lm_head);
+  m->lm_head8 = (s.fp8 || s.int4_group) ? (const uint8_t*)(ws + p.lm_head8) : nullptr;
+  m->g_lm = s.int4_group ? ws + p.g_lm : nullptr;
   m->lm_head_lo = s.wsplit ? (const uint16_t*)(ws + p.lm_head_lo) : nullptr;
   m->final_norm = (const float*)(ws + p.final_norm);
   m->rope = (const float2*)(ws + p.rope);

@@ -84,8 +84,9 @@ __device__ __forceinline__ int64_t kv_slot(const int32_t* __restrict__ row, int 
 // ------------------------------------------------------------------------------------------------
 struct LayerW {
   const uint16_t *wqkv, *wqkv_lo, *wo, *wo_lo, *wgu, *wgu_lo, *wd, *wd_lo;  // packed fp16 (lo planes only for fp32 sources)
-  const uint8_t *wqkv8, *wo8, *wgu8, *wd8;  // FP8 weight-only models: packed codes for the decode path ...
-  float sqkv, so, sgu, sd;                  // ... and the matrices' scales (1 otherwise)
+  const uint8_t *wqkv8, *wo8, *wgu8, *wd8;  // weight-only quantised models: packed codes for the decode path ...
+  float sqkv, so, sgu, sd;                  // ... FP8: the matrices' scales (1 otherwise)
+  const void *gqkv, *go, *ggu, *gd;         // ... int4: group scales as fp16, [chunk of 4 k blocks][packed row][4]
   const float *attn_norm, *ffn_norm;
 };
 
@@ -101,8 +102,10 @@ struct www_model {
   int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, max_pos, maxB, MTmax, maxT;
   bool wsplit;
   bool fp8;  // FP8 weight-only source
+  int int4_group;  // 128 or 32 for an int4 weight-only source, else 0
   const uint8_t* lm_head8;
   float s_lm;
+  const void* g_lm;
   // weights (inside the workspace)
   LayerW* layers;  // host array
   const void* embed;  // [V][d] in the source dtype
@@ -158,6 +161,8 @@ void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in f
 
 // host-side launchers (decode.hip / prefill.hip / pack.hip)
 void set_error(const char* fmt, ...);
+int launch_pack_int4(const void* codes, const void* scales_bf16, int N, int K, int KB, int group, int mode, int hd, int n_rot_rows, int F,
+                     uint16_t* f16_plane, uint8_t* codes_out, void* scales_out, hipStream_t st);
 int launch_pack_fp8(const void* src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F, uint8_t* out, hipStream_t st);
 int decode_attn_resident_waves(int hd, int G);
 int decode_probe_placement(int32_t* scratch_dev, int n, hipStream_t st);

@@ -80,6 +80,7 @@ struct GemmP {
   const u32x4* W;    // packed weights, 16-byte units (fp16 fragments, or FP8 codes of two k blocks)
   const u32x4* Wlo;  // low-order plane (fp32 sources) or null
   float wfactor;     // FP8 weights: the matrix's scale, applied to the result
+  const u32x2* Wscale;  // int4 weights: four fp16 group scales per (chunk of 4 k blocks, row)
   int NRG, KB;       // row groups of 16, k blocks of 32
   const u32x4* X;    // packed activations
   int MT, M;         // token groups in X, valid tokens
@@ -123,13 +124,33 @@ __device__ __forceinline__ f16x8 fp8x8_to_f16x8(uint32_t lo, uint32_t hi) {
   return __builtin_shufflevector(__builtin_shufflevector(a, b, 0, 1, 2, 3), __builtin_shufflevector(c, d, 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// WMODE: 0 = fp16 weights, 1 = fp16 hi + lo planes (fp32 sources), 2 = FP8 codes, two k blocks per 16-byte unit,
-// widened to fp16 in registers just before the MFMAs (the matrix's scale multiplies the result in the epilogue)
-enum { WMODE_F16 = 0, WMODE_SPLIT = 1, WMODE_FP8 = 2 };
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+
+// 8 four-bit codes (one 32-bit word, the code of column e in nibble e) -> 8 fp16 values (code - 8) * scale.  A code n
+// is planted in the mantissa of the fp16 number 1024 (0x6400 | n = 1024 + n, exact), 1032 is subtracted and the result
+// multiplied by the group's scale, two values per instruction; with a scale of 8 significant bits (bf16) the product
+// is exact.
+__device__ __forceinline__ f16x8 int4x8_to_f16x8(uint32_t w, f16x2 scale) {
+  const uint32_t even = w & 0x0F0F0F0Fu, odd = (w >> 4) & 0x0F0F0F0Fu;  // codes of columns 0,2,4,6 / 1,3,5,7, one per byte
+  const f16x2 off = {(_Float16)1032.f, (_Float16)1032.f};
+  f16x2 v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // low half: byte i of `even`, high half: byte i of `odd`
+    const uint32_t pair = __builtin_amdgcn_perm(odd, even, 0x0C040C00u + 0x00010001u * i) | 0x64006400u;
+    v[i] = (__builtin_bit_cast(f16x2, pair) - off) * scale;
+  }
+  return __builtin_shufflevector(__builtin_shufflevector(v[0], v[1], 0, 1, 2, 3), __builtin_shufflevector(v[2], v[3], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// WMODE: 0 = fp16 weights; 1 = fp16 hi + lo planes (fp32 sources); 2 = FP8 codes, two k blocks per 16-byte unit, widened
+// to fp16 in registers just before the MFMAs (the matrix's scale multiplies the result in the epilogue); 3 = int4 codes,
+// four k blocks (one chunk) per 16-byte unit, widened and multiplied by their group's scale in registers
+enum { WMODE_F16 = 0, WMODE_SPLIT = 1, WMODE_FP8 = 2, WMODE_INT4 = 3 };
 
 template <int MTK, int WMODE, int EPI>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
-  constexpr bool WSPLIT = WMODE == WMODE_SPLIT, W8 = WMODE == WMODE_FP8;
+  constexpr bool WSPLIT = WMODE == WMODE_SPLIT, W8 = WMODE == WMODE_FP8, W4 = WMODE == WMODE_INT4;
   constexpr int R = 2, KC = 4, WP = WSPLIT ? 2 : 1;
   constexpr int CHUNK_UNITS = KC * MTK * 128;      // 16-byte units of activations per k chunk
   constexpr int NSTG = CHUNK_UNITS / 256;
@@ -223,6 +244,17 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   // Loads past the end of this split's k range are redirected to its last valid block (in bounds) and the
   // matching MFMAs are skipped in compute(): no per-element selects in the streaming loop.
   auto load_w = [&](u32x4(&w)[KC][R][WP], int c) {
+    if constexpr (W4) {
+      // one 16-byte unit carries the whole chunk (entry 0 of the set); entry 1 takes the four group scales (8 bytes)
+      const int chunk = min((kb_begin + c * KC) >> 2, (kb_end - 1) >> 2);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        w[0][r][0] = p.W[((int64_t)chunk * p.NRG + rgc[r]) * 64 + lane];
+        const u32x2 sc = p.Wscale[((int64_t)chunk * p.NRG + rgc[r]) * 16 + (lane & 15)];
+        w[1][r][0] = u32x4{sc.x, sc.y, 0u, 0u};
+      }
+      return;
+    }
     if constexpr (W8) {
       // one 16-byte unit carries two k blocks: entries 0 and 2 of the set hold the chunk's two units, 1 and 3 stay unused
       // (kb_begin is a multiple of 4, so a chunk starts on a pair)
@@ -283,13 +315,23 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
           a8[r] = (kk & 1) ? fp8x8_to_f16x8(raw.z, raw.w) : fp8x8_to_f16x8(raw.x, raw.y);
         }
       }
+      if constexpr (W4) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const u32x4 raw = w[0][r][0], sc = w[1][r][0];
+          const uint32_t word = kk == 0 ? raw.x : kk == 1 ? raw.y : kk == 2 ? raw.z : raw.w;
+          const uint32_t s2 = kk < 2 ? sc.x : sc.y;
+          const uint32_t s16 = (kk & 1) ? (s2 >> 16) : (s2 & 0xFFFFu);
+          a8[r] = int4x8_to_f16x8(word, __builtin_bit_cast(f16x2, s16 | (s16 << 16)));
+        }
+      }
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
         const f16x8 bhi = as_f16x8(bq[kk & 1][tb][0]), blo = as_f16x8(bq[kk & 1][tb][1]);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           f16x8 a;
-          if constexpr (W8) a = a8[r];
+          if constexpr (W8 || W4) a = a8[r];
           else a = as_f16x8(w[kk][r][0]);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, acc[r][tb], 0, 0, 0);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, acc[r][tb], 0, 0, 0);
@@ -960,7 +1002,9 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
   dim3 grid(8 * ((row_tiles + 7) / 8) * p.ksplit * zb), block(256);
 #define LAUNCH(MTK_, WM_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WM_, EPI>), grid, block, 0, st, p);
-  if (m->fp8) {
+  if (m->int4_group) {
+    if (mtk == 1) LAUNCH(1, WMODE_INT4) else if (mtk == 2) LAUNCH(2, WMODE_INT4) else LAUNCH(4, WMODE_INT4)
+  } else if (m->fp8) {
     if (mtk == 1) LAUNCH(1, WMODE_FP8) else if (mtk == 2) LAUNCH(2, WMODE_FP8) else LAUNCH(4, WMODE_FP8)
   } else if (m->wsplit) {
     if (mtk == 1) LAUNCH(1, WMODE_SPLIT) else if (mtk == 2) LAUNCH(2, WMODE_SPLIT) else LAUNCH(4, WMODE_SPLIT)
@@ -1030,7 +1074,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
     {
       GemmP p = {};
-      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wqkv8 : (const void*)w.wqkv); p.Wlo = (const u32x4*)w.wqkv_lo; p.wfactor = w.sqkv;
+      p.W = (const u32x4*)(w.wqkv8 ? (const void*)w.wqkv8 : (const void*)w.wqkv); p.Wlo = (const u32x4*)w.wqkv_lo; p.wfactor = w.sqkv; p.Wscale = (const u32x2*)w.gqkv;
       p.NRG = m->QKVN / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
@@ -1059,7 +1103,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wo8 : (const void*)w.wo); p.Wlo = (const u32x4*)w.wo_lo; p.wfactor = w.so;
+      p.W = (const u32x4*)(w.wo8 ? (const void*)w.wo8 : (const void*)w.wo); p.Wlo = (const u32x4*)w.wo_lo; p.wfactor = w.so; p.Wscale = (const u32x2*)w.go;
       p.NRG = d / 16; p.KB = m->QD / 32;
       p.X = (const u32x4*)m->xo; p.M = batch;
       p.h = m->h; p.gain_next = w.ffn_norm; p.xnext = (uint16_t*)m->xq; p.ssq_out = m->ssq; p.d = d;
@@ -1069,7 +1113,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wgu8 : (const void*)w.wgu); p.Wlo = (const u32x4*)w.wgu_lo; p.wfactor = w.sgu;
+      p.W = (const u32x4*)(w.wgu8 ? (const void*)w.wgu8 : (const void*)w.wgu); p.Wlo = (const u32x4*)w.wgu_lo; p.wfactor = w.sgu; p.Wscale = (const u32x2*)w.ggu;
       p.NRG = 2 * m->F / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
@@ -1079,7 +1123,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     }
     {
       GemmP p = {};
-      p.W = (const u32x4*)(m->fp8 ? (const void*)w.wd8 : (const void*)w.wd); p.Wlo = (const u32x4*)w.wd_lo; p.wfactor = w.sd;
+      p.W = (const u32x4*)(w.wd8 ? (const void*)w.wd8 : (const void*)w.wd); p.Wlo = (const u32x4*)w.wd_lo; p.wfactor = w.sd; p.Wscale = (const u32x2*)w.gd;
       p.NRG = d / 16; p.KB = m->Fp / 32;
       p.X = (const u32x4*)m->xa; p.M = batch;
       p.h = m->h; p.gain_next = (l + 1 < m->L) ? m->layers[l + 1].attn_norm : m->final_norm;
@@ -1091,7 +1135,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
   float* lg = logits ? logits : m->logits_buf;
   {
     GemmP p = {};
-    p.W = (const u32x4*)(m->fp8 ? (const void*)m->lm_head8 : (const void*)m->lm_head); p.Wlo = (const u32x4*)m->lm_head_lo; p.wfactor = m->s_lm;
+    p.W = (const u32x4*)(m->lm_head8 ? (const void*)m->lm_head8 : (const void*)m->lm_head); p.Wlo = (const u32x4*)m->lm_head_lo; p.wfactor = m->s_lm; p.Wscale = (const u32x2*)m->g_lm;
     p.NRG = m->V / 16; p.KB = d / 32;
     p.X = (const u32x4*)m->xq; p.M = batch;
     p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;

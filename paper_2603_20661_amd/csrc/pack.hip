@@ -100,6 +100,82 @@ int launch_pack_fp8(const void* src, int N, int K, int KB, int mode, int hd, int
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// int4 weight-only sources: codes[N][K/2] (two per byte, even column low), scales[N][K/group] in bf16.
+__device__ __forceinline__ int int4_code(const uint8_t* __restrict__ codes, int64_t row, int K, int k) {
+  const uint8_t b = codes[(row * K + k) >> 1];
+  return (k & 1) ? (b >> 4) : (b & 0xF);
+}
+
+// fp16 plane for the prefill GEMMs, in the usual fragment order: (c - 8) * scale (a 4-bit integer times a bf16: exact in
+// fp16 unless the scale is below fp16's normal range)
+__global__ void pack_int4_f16_kernel(const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, int N, int K, int KB, int group,
+                                     int mode, int hd, int n_rot_rows, int F, uint16_t* __restrict__ hi) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)(N / 16) * KB * 64) return;
+  const int lane = (int)(idx & 63);
+  const int64_t frag = idx >> 6;
+  const int NRG = N / 16;
+  const int rg = (int)(frag % NRG), kb = (int)(frag / NRG);
+  const int64_t srow = source_row(rg * 16 + (lane & 15), mode, hd, n_rot_rows, F);
+  const int k0 = kb * 32 + (lane >> 4) * 8;
+  union { uint16_t s[8]; uint4 v; } h;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int k = k0 + e;
+    float x = 0.f;
+    if (k < K) x = (float)(int4_code(codes, srow, K, k) - 8) * bf16_bits_to_float(scales[srow * (K / group) + k / group]);
+    h.s[e] = f32_to_f16_sat(x);
+  }
+  *reinterpret_cast<uint4*>(hi + idx * 8) = h.v;
+}
+
+// Decode order: 16-byte unit ((chunk j of 4 k blocks, row group rg), lane) holds the lane's 8 codes of k blocks 4j .. 4j+3,
+// one 32-bit word per k block, the code of the lane's e-th column in nibble e; zero weights (code 8) past K.
+// Group scales for the decode GEMM: fp16, [chunk][packed row][4] = the scale of each of the chunk's 4 k blocks.
+__global__ void pack_int4_kernel(const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales, int N, int K, int KB, int group,
+                                 int mode, int hd, int n_rot_rows, int F, uint8_t* __restrict__ out, uint16_t* __restrict__ sc_out) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int NRG = N / 16, KB4 = (KB + 3) / 4;
+  if (idx >= (int64_t)NRG * KB4 * 64) return;
+  const int lane = (int)(idx & 63);
+  const int64_t unit = idx >> 6;
+  const int rg = (int)(unit % NRG), kb4 = (int)(unit / NRG);
+  const int p = rg * 16 + (lane & 15);
+  const int64_t srow = source_row(p, mode, hd, n_rot_rows, F);
+  uint32_t w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int k0 = (kb4 * 4 + j) * 32 + (lane >> 4) * 8;
+    uint32_t v = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v |= (uint32_t)((k0 + e < K) ? int4_code(codes, srow, K, k0 + e) : 8) << (4 * e);
+    w[j] = v;
+  }
+  *reinterpret_cast<uint4*>(out + idx * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+  if (lane < 16) {
+    union { uint16_t s[4]; uint2 v; } sc;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = (kb4 * 4 + j) * 32;
+      sc.s[j] = k < K ? f32_to_f16_sat(bf16_bits_to_float(scales[srow * (K / group) + k / group])) : (uint16_t)0;
+    }
+    *reinterpret_cast<uint2*>(sc_out + ((int64_t)kb4 * N + p) * 4) = sc.v;
+  }
+}
+
+int launch_pack_int4(const void* codes, const void* scales_bf16, int N, int K, int KB, int group, int mode, int hd, int n_rot_rows, int F,
+                     uint16_t* f16_plane, uint8_t* codes_out, void* scales_out, hipStream_t st) {
+  if (f16_plane) {
+    const int64_t total = (int64_t)(N / 16) * KB * 64;
+    hipLaunchKernelGGL(pack_int4_f16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t*)codes,
+                       (const uint16_t*)scales_bf16, N, K, KB, group, mode, hd, n_rot_rows, F, f16_plane);
+  }
+  const int64_t total = (int64_t)(N / 16) * ((KB + 3) / 4) * 64;
+  hipLaunchKernelGGL(pack_int4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint8_t*)codes,
+                     (const uint16_t*)scales_bf16, N, K, KB, group, mode, hd, n_rot_rows, F, codes_out, (uint16_t*)scales_out);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 __global__ void debug_slots_kernel(const int32_t* __restrict__ row, const int32_t* __restrict__ pos, int n, int64_t* __restrict__ out) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = kv_slot(row, pos[i]);

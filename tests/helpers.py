@@ -8,8 +8,8 @@ from paper_2603_20661_amd import synth
 
 
 def oracle_view(shape, blob):
-    """What the model oracle is given: the blob itself, or, for an fp8 weight-only model, its decoded fp32 form."""
-    if shape.weight_dtype == synth.WDTYPE_FP8WO:
+    """What the model oracle is given: the blob itself, or, for a weight-only quantised model, its decoded fp32 form."""
+    if shape.weight_dtype in (synth.WDTYPE_FP8WO, synth.WDTYPE_INT4WO_128, synth.WDTYPE_INT4WO_32):
         from oracle import quant
         return quant.dequantize_blob(shape, blob)
     return shape, blob

@@ -177,6 +177,31 @@ def test_fp8_weight_only_models(shape, lens, steps, chunk):
     check(run_job(shape, lens, steps, seed=120 + len(lens), chunk=chunk, gain_std=0.1), f"{shape.name} lens={len(lens)} chunk={chunk}")
 
 
+# int4 groups need ffn widths that are multiples of the group size
+Q128_HD128 = synth.ModelShape("q128hd128", 3, 512, 8, 2, 128, 1408, 2048, 1e-5, 5e5, synth.WDTYPE_INT4WO_128, seed=26)
+Q32_HD64 = synth.ModelShape("q32hd64", 2, 256, 8, 4, 64, 736, 1024, 1e-5, 1e4, synth.WDTYPE_INT4WO_32, seed=28)
+WIDE8B_Q128 = dataclasses.replace(WIDE8B, name="wide8bq128", weight_dtype=synth.WDTYPE_INT4WO_128, seed=35)
+WIDE1B_Q32 = dataclasses.replace(WIDE1B, name="wide1bq32", weight_dtype=synth.WDTYPE_INT4WO_32, seed=36)
+
+
+@pytest.mark.parametrize("shape,lens,steps,chunk", [
+    (Q32_HD64, [1, 17, 150, 40, 9], 6, None),
+    (Q128_HD128, [200, 31, 64, 5, 90, 33, 16, 1] * 3, 5, None),
+    (Q128_HD128, [130, 47, 300], 4, 37),
+])
+def test_int4_weight_only_models(shape, lens, steps, chunk):
+    """Weights stored as 4-bit codes with a bf16 scale per group of 128 / 32: the decode path widens and scales the codes
+    in registers, the prefill path reads an fp16 copy; the oracle runs the decoded fp32 model."""
+    check(run_job(shape, lens, steps, seed=160 + len(lens), chunk=chunk, gain_std=0.1), f"{shape.name} lens={len(lens)} chunk={chunk}")
+
+
+@pytest.mark.parametrize("shape,batch", [(WIDE8B_Q128, 64), (WIDE1B_Q32, 32), (WIDE8B_Q128, 70)])
+def test_int4_weight_only_full_width_layers(shape, batch):
+    lens = 1 + synth.uniform_i32(batch, 14, batch, 40)
+    lens[0], lens[1] = 1, 16
+    check(run_job(shape, lens, 3, seed=180 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+
+
 @pytest.mark.parametrize("shape,batch", [(WIDE8B_FP8, 64), (WIDE1B_FP8, 32), (WIDE8B_FP8, 70)])
 def test_fp8_weight_only_full_width_layers(shape, batch):
     lens = 1 + synth.uniform_i32(batch, 13, batch, 40)
