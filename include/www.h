@@ -295,6 +295,20 @@ int www_sched_commit(www_sched* sched, int32_t* n_finished, uint64_t* finished_r
 /* The figures a Model Manager polls. */
 int www_get_stats(const www_sched* sched, www_stats* out);
 
+/* ------------------------------------------------------------------------------------------------
+ * Sampling beyond greedy (App. C lists temperature and top-p among the generation parameters; the paper's own runs
+ * use temperature 0, which is the greedy token www_decode_step already returns).  Definition used here, per row:
+ * p = softmax(logits / temperature); the nucleus is {i : p_i >= tau} for the largest tau among the probabilities whose
+ * members' mass reaches top_p (equal probabilities enter together); the token is the first member, in index order,
+ * whose running mass exceeds u01[row] times the nucleus mass.  No sort is involved and every sum has a fixed order, so
+ * a call is reproducible; against an exact evaluation the choice can differ only where a sum lies within fp32
+ * rounding of a decision point.
+ *   logits_dev fp32 [batch][vocab]; u01_dev fp32 [batch], the caller's uniform numbers in [0, 1);
+ *   scratch_dev fp32 [batch][vocab], overwritten (unnormalised probabilities); tokens_dev int32 [batch].
+ * temperature > 0, 0 < top_p <= 1; batch == 0 is a no-op.  Errors: INVALID_ARG, HIP. */
+int www_sample_top_p(const float* logits_dev, int32_t batch, int32_t vocab, float temperature, float top_p, const float* u01_dev,
+                     float* scratch_dev, int32_t* tokens_dev, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,10 +28,11 @@ def nucleus_fast(logits_row, temperature: float, top_p: float):
     """The same set for long rows: cumulative mass over the sorted values instead of one pass per distinct value."""
     z = np.asarray(logits_row, dtype=np.float64) / float(temperature)
     e = np.exp(z - z.max())
-    need = float(top_p) * e.sum()
     order = np.argsort(-e, kind="stable")
     es = e[order]
     cum = np.cumsum(es)
+    need = float(top_p) * cum[-1]                    # the total in the same summation order as the masses below, so that
+                                                     # top_p = 1 is reached by the whole vocabulary and by nothing less
     # mass of {e >= es[k]} = cum at the LAST position holding the value es[k]
     last_of_value = np.searchsorted(-es, -es, side="right") - 1
     mass = cum[last_of_value]

@@ -21,7 +21,7 @@ EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step"
            "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
            "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
            "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
-           "www_get_stats")
+           "www_get_stats", "www_sample_top_p")
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
 
@@ -103,6 +103,8 @@ def _load_library():
     L.www_sched_table_row.argtypes = [vp, i32, ip]
     L.www_sched_commit.argtypes = [vp, ip, u64a]
     L.www_get_stats.argtypes = [vp, ctypes.POINTER(WwwStats)]
+    L.www_sample_top_p.argtypes = [vp, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
+    L.www_sample_top_p.restype = ctypes.c_int
     for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read",
                  "www_debug_profile", "www_debug_profile_read", "www_judge_verdict", "www_ledger_create", "www_ledger_stakes",
                  "www_pos_sample", "www_ledger_serve", "www_ledger_duel", "www_ledger_read_ops", "www_sched_create", "www_sched_submit",
@@ -221,6 +223,14 @@ def www_judge_verdict(logits, token_a: int, token_b: int, verdict, margin=None, 
     batch, vocab = logits.shape
     _check(lib.www_judge_verdict(_ptr(logits, torch.float32), batch, vocab, token_a, token_b, _ptr(verdict, torch.int32),
                                  _ptr(margin, torch.float32), _stream(stream)))
+
+
+def www_sample_top_p(logits, temperature: float, top_p: float, u01, scratch, tokens, stream=None):
+    """logits fp32 [batch, vocab], u01 fp32 [batch], scratch fp32 [batch, vocab] (overwritten) -> tokens int32 [batch]"""
+    batch, vocab = logits.shape
+    assert scratch.numel() >= batch * vocab
+    _check(lib.www_sample_top_p(_ptr(logits, torch.float32), batch, vocab, temperature, top_p, _ptr(u01, torch.float32),
+                                _ptr(scratch, torch.float32), _ptr(tokens, torch.int32), _stream(stream)))
 
 
 class Ledger:
