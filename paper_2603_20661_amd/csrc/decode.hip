@@ -148,19 +148,27 @@ __device__ __forceinline__ f16x8 int4x8_to_f16x8(uint32_t w, f16x2 scale) {
 // four k blocks (one chunk) per 16-byte unit, widened and multiplied by their group's scale in registers
 enum { WMODE_F16 = 0, WMODE_SPLIT = 1, WMODE_FP8 = 2, WMODE_INT4 = 3 };
 
-template <int MTK, int WMODE, int EPI>
-__global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
+// KH = 1: four wavefronts, each multiplies its two row groups with all four k blocks of a chunk.  KH = 2: eight
+// wavefronts (two per SIMD); wavefront w and w + 4 own the same two row groups and take k blocks 0,1 / 2,3 of every
+// chunk, so each issues half of the MFMAs and one can issue while its SIMD partner waits for memory; the two partial
+// tiles are added through LDS behind the loop and wavefronts 4..7 retire.
+template <int MTK, int WMODE, int EPI, int KH>
+__global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const GemmP p) {
   constexpr bool WSPLIT = WMODE == WMODE_SPLIT, W8 = WMODE == WMODE_FP8, W4 = WMODE == WMODE_INT4;
   constexpr int R = 2, KC = 4, WP = WSPLIT ? 2 : 1;
+  constexpr int NT = 256 * KH;                     // threads
+  constexpr int KPW = KC / KH;                     // k blocks of a chunk per wavefront
+  static_assert(KH == 1 || (KH == 2 && !W4), "the int4 unit spans the whole chunk");
   constexpr int CHUNK_UNITS = KC * MTK * 128;      // 16-byte units of activations per k chunk
-  constexpr int NSTG = CHUNK_UNITS / 256;
+  constexpr int NSTG = (CHUNK_UNITS + NT - 1) / NT;
   __shared__ u32x4 lds[2][CHUNK_UNITS];
   __shared__ float s_scale[64];
   // after the main loop the staging buffers are dead and are reused for the epilogue's small reductions
   float(*red)[64] = reinterpret_cast<float(*)[64]>(&lds[0][0]);
   volatile int* s_last = reinterpret_cast<volatile int*>(&lds[1][0]);
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = (tid >> 6) & 3, khalf = KH == 1 ? 0 : tid >> 8, lane = tid & 63;
+  const int k_first = khalf * KPW;                 // first k block of a chunk this wavefront multiplies
   // Workgroup id -> work item.  Consecutive workgroup ids are dealt round-robin to the XCDs (8 here; any power of two
   // up to 8 divides 8), so ids that are equal modulo 8 run behind the same L2.  All k splits of a row tile get such
   // ids: id = c + 8 * ((zb * tiles_per_xcd + lt) * ksplit + split) for row tile c + 8 * lt.  Their partial tiles then
@@ -204,7 +212,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     pos_pre[tb] = 0;
     if constexpr (EPI == EPI_QKV) pos_pre[tb] = p.seq_lens[tok_c[tb]] - 1;
   }
-  if (p.ssq_in && wave < MTK) {
+  if (p.ssq_in && wave < MTK && khalf == 0) {
     const int t = min((tb0 + wave) * 16 + (lane & 15), p.M - 1);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   int blk_pre[MTK];
   // before the first barrier: reduce the sums and publish the scales; table loads for the KV slots go out
   auto finish_prefetch = [&]() __attribute__((always_inline)) {
-    if (p.ssq_in && wave < MTK) {
+    if (p.ssq_in && wave < MTK && khalf == 0) {
       float s = 0.f;
 #pragma unroll
       for (int c = 0; c < 4; ++c)
@@ -259,28 +267,28 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
       // one 16-byte unit carries two k blocks: entries 0 and 2 of the set hold the chunk's two units, 1 and 3 stay unused
       // (kb_begin is a multiple of 4, so a chunk starts on a pair)
 #pragma unroll
-      for (int kk = 0; kk < KC; kk += 2) {
-        const int pair = min((kb_begin + c * KC + kk) >> 1, (kb_end - 1) >> 1);
+      for (int j = 0; j < KPW; j += 2) {
+        const int pair = min((kb_begin + c * KC + k_first + j) >> 1, (kb_end - 1) >> 1);
 #pragma unroll
-        for (int r = 0; r < R; ++r) w[kk][r][0] = p.W[((int64_t)pair * p.NRG + rgc[r]) * 64 + lane];
+        for (int r = 0; r < R; ++r) w[j][r][0] = p.W[((int64_t)pair * p.NRG + rgc[r]) * 64 + lane];
       }
       return;
     }
 #pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
+    for (int j = 0; j < KPW; ++j) {  // register slot j holds k block k_first + j of the chunk
+      const int kbc = min(kb_begin + c * KC + k_first + j, kb_end - 1);
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         const int64_t idx = ((int64_t)kbc * p.NRG + rgc[r]) * 64 + lane;
-        w[kk][r][0] = p.W[idx];
-        if constexpr (WSPLIT) w[kk][r][1] = p.Wlo[idx];
+        w[j][r][0] = p.W[idx];
+        if constexpr (WSPLIT) w[j][r][1] = p.Wlo[idx];
       }
     }
   };
   auto load_stage = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NSTG; ++i) {
-      const int u = tid + i * 256;
+      const int u = min(tid + i * NT, CHUNK_UNITS - 1);  // (more threads than units when MTK = 1 and KH = 2)
       const int kk = u / (MTK * 128), within = u % (MTK * 128);
       const int kbc = min(kb_begin + c * KC + kk, kb_end - 1);
       stg[i] = p.X[((int64_t)kbc * p.MT + tb0) * 128 + within];
@@ -288,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
   };
   auto store_stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < NSTG; ++i) lds[buf][tid + i * 256] = stg[i];
+    for (int i = 0; i < NSTG; ++i) lds[buf][min(tid + i * NT, CHUNK_UNITS - 1)] = stg[i];
   };
   // nvalid = k blocks of the chunk that lie inside the range: KC for every chunk but possibly the last.
   // The B fragments (activations) of k block kk+1 are fetched from LDS while the MFMAs of k block kk run.
@@ -301,41 +309,41 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
         bq[set][tb][1] = lds[buf][(kk * MTK + tb) * 128 + 64 + lane];
       }
     };
-    fetch(0, 0);
+    fetch(0, k_first);
 #pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      if (kk >= nvalid) break;
-      if (kk + 1 < KC) fetch((kk + 1) & 1, kk + 1);
+    for (int j = 0; j < KPW; ++j) {  // k block k_first + j of the chunk, operands in register slot j
+      if (k_first + j >= nvalid) break;
+      if (j + 1 < KPW) fetch((j + 1) & 1, k_first + j + 1);
       __builtin_amdgcn_sched_barrier(0);
       f16x8 a8[R];
       if constexpr (W8) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const u32x4 raw = w[kk & ~1][r][0];
-          a8[r] = (kk & 1) ? fp8x8_to_f16x8(raw.z, raw.w) : fp8x8_to_f16x8(raw.x, raw.y);
+          const u32x4 raw = w[j & ~1][r][0];
+          a8[r] = (j & 1) ? fp8x8_to_f16x8(raw.z, raw.w) : fp8x8_to_f16x8(raw.x, raw.y);
         }
       }
-      if constexpr (W4) {
+      if constexpr (W4) {  // (KH = 1: j is the k block)
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           const u32x4 raw = w[0][r][0], sc = w[1][r][0];
-          const uint32_t word = kk == 0 ? raw.x : kk == 1 ? raw.y : kk == 2 ? raw.z : raw.w;
-          const uint32_t s2 = kk < 2 ? sc.x : sc.y;
-          const uint32_t s16 = (kk & 1) ? (s2 >> 16) : (s2 & 0xFFFFu);
+          const uint32_t word = j == 0 ? raw.x : j == 1 ? raw.y : j == 2 ? raw.z : raw.w;
+          const uint32_t s2 = j < 2 ? sc.x : sc.y;
+          const uint32_t s16 = (j & 1) ? (s2 >> 16) : (s2 & 0xFFFFu);
           a8[r] = int4x8_to_f16x8(word, __builtin_bit_cast(f16x2, s16 | (s16 << 16)));
         }
       }
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
-        const f16x8 bhi = as_f16x8(bq[kk & 1][tb][0]), blo = as_f16x8(bq[kk & 1][tb][1]);
+        const f16x8 bhi = as_f16x8(bq[j & 1][tb][0]), blo = as_f16x8(bq[j & 1][tb][1]);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           f16x8 a;
           if constexpr (W8 || W4) a = a8[r];
-          else a = as_f16x8(w[kk][r][0]);
+          else a = as_f16x8(w[j][r][0]);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bhi, acc[r][tb], 0, 0, 0);
           acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, blo, acc[r][tb], 0, 0, 0);
-          if constexpr (WSPLIT) acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(w[kk][r][1]), bhi, acc[r][tb], 0, 0, 0);
+          if constexpr (WSPLIT) acc[r][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(w[j][r][1]), bhi, acc[r][tb], 0, 0, 0);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -388,6 +396,25 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const GemmP p) {
     finish_prefetch();
     __syncthreads();
     read_scales();
+  }
+
+  if constexpr (KH == 2) {
+    // the staging buffers are dead: wavefronts 4..7 hand their partial tile to wavefronts 0..3 (same rows) and retire;
+    // the barriers further down then only count the wavefronts that are left
+    u32x4* xch = &lds[0][0];  // [wavefront 0..3][r][tb][lane]
+    if (khalf == 1) {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int tb = 0; tb < MTK; ++tb) xch[((wave * R + r) * MTK + tb) * 64 + lane] = __builtin_bit_cast(u32x4, acc[r][tb]);
+    }
+    __syncthreads();
+    if (khalf == 1) return;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int tb = 0; tb < MTK; ++tb) acc[r][tb] += __builtin_bit_cast(f32x4, xch[((wave * R + r) * MTK + tb) * 64 + lane]);
+    __syncthreads();  // `red` and `s_last` below reuse the same LDS
   }
 
   // accumulator layout: acc[r][tb][i] = Y^T[row][token], row = (rg0+r)*16 + (lane/16)*4 + i, token = (tb0+tb)*16 + lane%16
@@ -1000,16 +1027,21 @@ static void launch_gemm(www_model* m, GemmP& p, int MT, hipStream_t st) {
   p.zbs = zb;
   p.fence_handover = m->handover_fence;
   if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
-  dim3 grid(8 * ((row_tiles + 7) / 8) * p.ksplit * zb), block(256);
-#define LAUNCH(MTK_, WM_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WM_, EPI>), grid, block, 0, st, p);
+  dim3 grid(8 * ((row_tiles + 7) / 8) * p.ksplit * zb);
+#define LAUNCH(MTK_, WM_, KH_) hipLaunchKernelGGL((skinny_gemm_kernel<MTK_, WM_, EPI, KH_>), grid, dim3(256 * KH_), 0, st, p);
+  // With more than 32 tokens the MFMAs of a chunk take a third of a wavefront's time; in the gate/up GEMM (no split-K,
+  // 32 chunks per workgroup) two wavefronts per SIMD (KH = 2) hide them behind each other's waits: 53 -> 49.5 us at 64
+  // tokens of the 8B shape.  The split-K GEMMs walk 4 - 14 chunks and are bound by their fixed costs; the hand-over
+  // between the wavefront halves costs them as much as it saves, so they stay at KH = 1.
+  constexpr int kh4 = EPI == EPI_SWIGLU ? 2 : 1;
   if (m->int4_group) {
-    if (mtk == 1) LAUNCH(1, WMODE_INT4) else if (mtk == 2) LAUNCH(2, WMODE_INT4) else LAUNCH(4, WMODE_INT4)
+    if (mtk == 1) LAUNCH(1, WMODE_INT4, 1) else if (mtk == 2) LAUNCH(2, WMODE_INT4, 1) else LAUNCH(4, WMODE_INT4, 1)
   } else if (m->fp8) {
-    if (mtk == 1) LAUNCH(1, WMODE_FP8) else if (mtk == 2) LAUNCH(2, WMODE_FP8) else LAUNCH(4, WMODE_FP8)
+    if (mtk == 1) LAUNCH(1, WMODE_FP8, 1) else if (mtk == 2) LAUNCH(2, WMODE_FP8, 1) else LAUNCH(4, WMODE_FP8, kh4)
   } else if (m->wsplit) {
-    if (mtk == 1) LAUNCH(1, WMODE_SPLIT) else if (mtk == 2) LAUNCH(2, WMODE_SPLIT) else LAUNCH(4, WMODE_SPLIT)
+    if (mtk == 1) LAUNCH(1, WMODE_SPLIT, 1) else if (mtk == 2) LAUNCH(2, WMODE_SPLIT, 1) else LAUNCH(4, WMODE_SPLIT, 1)
   } else {
-    if (mtk == 1) LAUNCH(1, WMODE_F16) else if (mtk == 2) LAUNCH(2, WMODE_F16) else LAUNCH(4, WMODE_F16)
+    if (mtk == 1) LAUNCH(1, WMODE_F16, 1) else if (mtk == 2) LAUNCH(2, WMODE_F16, 1) else LAUNCH(4, WMODE_F16, kh4)
   }
 #undef LAUNCH
 }
