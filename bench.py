@@ -47,18 +47,18 @@ CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
 # HBM traffic of the dominant decode kernel class (decode_attn_kernel + decode_attn_merge_kernel), from two
 # `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE; profiles/decode_attention_8b_traffic.md).
 # Counter units per launch, averaged over the 256 launches of those runs; scale = bytes per unit / 1024, from what the
-# same counter read for the calibration copy above (131 088.1 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
+# same counter read for the calibration copy above (131 088.8 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
 # of WRITE_SIZE for 262 144 KiB written); algorithmic bytes of those same launches for rescaling to another context.
 # Valid only for the kernels it was taken with: the hash covers the text of the attention plan / attention / merge kernels
 # in decode.hip and of the layout helpers in common.h; the reading is reported as null when that text has changed.
 TRAFFIC = {
     "workload": "8b", "kernel": "decode_attention",
-    "fetch_units": 163132.1 + 1674.0, "write_units": 3112.7 + 1024.0,
-    "fetch_scale": 262144.0 / 131088.1, "write_scale": 1.0,
+    "fetch_units": 162676.4 + 1672.4, "write_units": 3107.9 + 1024.0,
+    "fetch_scale": 262144.0 / 131088.8, "write_scale": 1.0,
     "algorithmic_bytes_of_measured_launches": 80383 * 4096,
     "sources": (("paper_2603_20661_amd/csrc/decode.hip", "// Plan of the decode attention", "void argmax_take("),
                 ("paper_2603_20661_amd/csrc/common.h", "inline int64_t packed_w_elems(", "struct LayerW {")),
-    "sha256": "2aa824a20d2877c2f3fa35b41161f401fefd82776e851b17b6cbdca54340bc19",
+    "sha256": "dc3bc565fb80e21f5e3c66b4e97af4d8851cfe3cc53f9865f773c83170ebf23a",
 }
 
 

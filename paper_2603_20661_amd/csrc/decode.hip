@@ -740,13 +740,13 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
         const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
 #pragma unroll
         for (int f = 0; f < NKF; ++f) {
-          r.k0[f] = *reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8);
-          r.k1[f] = *reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8);
+          r.k0[f] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8));
+          r.k1[f] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kplane + off1 + (f * 64 + lane) * 8));
         }
 #pragma unroll
         for (int f = 0; f < NVF; ++f) {
-          r.v0[f] = *reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4);
-          r.v1[f] = *reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4);
+          r.v0[f] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vplane + off0 + (f * 64 + lane) * 4));
+          r.v1[f] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vplane + off1 + (f * 64 + lane) * 4));
         }
       };
       auto process = [&](KV& r, int pr) __attribute__((always_inline)) {
