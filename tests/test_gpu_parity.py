@@ -150,10 +150,12 @@ WIDE8B = dataclasses.replace(synth.M8B, name="wide8b", n_layers=2, seed=31)
 WIDE1B = dataclasses.replace(synth.M1B, name="wide1b", n_layers=2, seed=32)
 
 
-@pytest.mark.parametrize("shape,batch", [(WIDE8B, 64), (WIDE1B, 32)])
+@pytest.mark.parametrize("shape,batch", [(WIDE8B, 64), (WIDE1B, 32), (WIDE1B, 64)])
 def test_full_width_layers_at_bench_batch(shape, batch):
     """every matrix has its full 8B / 1B size (same tiles, split-K factors and token groups as the benchmark);
-    only the layer count is cut so the oracle finishes in about a minute"""
+    only the layer count is cut so the oracle finishes in about a minute.  The 1B-wide model at batch 64 is the case in
+    which the gate/up GEMM runs with eight wavefronts per workgroup AND split over k (its 128 row tiles do not fill the
+    device)."""
     lens = 1 + synth.uniform_i32(batch, 11, batch, 40)
     lens[0], lens[1] = 1, 16
     check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
