@@ -542,6 +542,12 @@ def main():
                     "traffic": measured_traffic(args.workload, dom, per_bytes[dom]),
                     "algorithmic_bytes_per_launch": int(per_bytes[dom]), "avg_launch_ms": kernels[dom]["avg_ms"]}
 
+    copy_peak = measured_copy_bandwidth(dev, stream)
+    if roofline:
+        # what an event pair around a near-empty kernel reads in the middle of a busy stream: the part of avg_launch_ms that
+        # is dispatch and event handling rather than the kernel (a kernel trace's durations are shorter by about this much)
+        roofline["event_pair_floor_ms"] = event_pair_floor(dev, stream)
+
     cpu = None
     if not args.no_cpu_baseline and shape.weight_dtype < 2:   # (the weight-only quantised workloads are not the bench line)
         cpu = cpu_baseline(shape, blob, lens, nsteps)
@@ -557,7 +563,9 @@ def main():
         "prefill_ms": round(pre_ms / args.steps, 3),
         "roofline": roofline,
         "roofline_decode_step": {"bound": "hbm", "achieved": round(step_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                 "frac": round(step_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_step": int(step_bytes)},
+                                 "frac": round(step_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_step": int(step_bytes),
+                                 "frac_of_measured_copy": round(step_gbs / copy_peak["GBps"], 4)},
+        "measured_copy_bandwidth": copy_peak,
         "roofline_prefill": {"bound": "mfma", "achieved": round(pre_tflops, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": round(pre_tflops / MFMA_PEAK_TFLOPS, 4), "algorithmic_flops": pf},
         "decode_kernels": kernels,
@@ -567,6 +575,58 @@ def main():
     }
     print(json.dumps(out), flush=True)
     model.close()
+
+
+def measured_copy_bandwidth(dev, stream):
+    """What a plain device-to-device copy reaches on this GPU (read plus written bytes over the time between two events):
+    the achievable figure beside the published 8 TB/s that the roofline fractions are quoted against."""
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    src.fill_(3)
+    times = []
+    with torch.cuda.stream(stream):
+        for it in range(7):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            dst.copy_(src)
+            e1.record(stream)
+            stream.synchronize()
+            if it >= 2:
+                times.append(e0.elapsed_time(e1))
+    del src, dst
+    torch.cuda.empty_cache()
+    ms = float(np.median(times))
+    return {"GBps": round(2 * nbytes / ms * 1e-6, 1), "what": "device-to-device copy of 1 GiB, read + written bytes, median of 5 after 2 warm-up"}
+
+
+def event_pair_floor(dev, stream):
+    busy = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+    tiny = torch.zeros(64, dtype=torch.int32, device=dev)
+    with torch.cuda.stream(stream):
+        busy.fill_(1)   # keeps the queue ahead of the device while the pairs are enqueued
+        busy.fill_(2)
+        evs = []
+        for _ in range(64):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            tiny.add_(1)
+            e1.record(stream)
+            evs.append((e0, e1))
+        stream.synchronize()
+    del busy
+    return round(float(np.median([a.elapsed_time(b) for a, b in evs])), 5)
+
+
+def cpu_model_name():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def cpu_baseline(shape, blob, lens, nsteps):
@@ -598,7 +658,7 @@ def cpu_baseline(shape, blob, lens, nsteps):
         steps_done += 1
     dt = time.time() - t0
     m.close()
-    return {"value": round(n * steps_done / dt, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    return {"value": round(n * steps_done / dt, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle", "cpu": cpu_model_name(),
             "sample": f"{steps_done} decode step(s) of the first {n} sequences (context {int(ctx.min())}..{int(ctx.max()) + steps_done - 1}), KV "
                       f"pre-filled with seeded N(0,1) values, {dt:.1f} s"}
 

@@ -20,7 +20,7 @@ class OrcConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab")] + \
                [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
-                ("kv_block_size", ctypes.c_int32), ("weight_dtype", ctypes.c_int32)]
+                ("kv_block_size", ctypes.c_int32), ("weight_dtype", ctypes.c_int32), ("qk_norm", ctypes.c_int32)]
 
 
 def build(force: bool = False) -> str:
@@ -132,7 +132,7 @@ class OracleModel:
         self.blob = np.ascontiguousarray(blob, dtype=np.uint8)
         cfg = OrcConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                         shape.ffn_dim, shape.vocab, shape.rms_eps, shape.rope_theta, shape.kv_block_size,
-                        shape.weight_dtype)
+                        shape.weight_dtype, int(getattr(shape, "qk_norm", 0)))
         self._h = lib().orc_create(ctypes.byref(cfg), self.blob.ctypes.data, max_seqs, max_ctx, num_blocks)
         if not self._h:
             raise ValueError("orc_create rejected the configuration")

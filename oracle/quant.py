@@ -85,7 +85,10 @@ def dequantize_blob(shape, blob):
     at += pad(2 * V * d)
     emit((emb.astype(np.uint32) << np.uint32(16)).view(np.float32))   # bf16 widened exactly
     for _ in range(L):
-        gains(d); matrix(qkv, d); matrix(d, qd); gains(d); matrix(2 * F, d); matrix(d, F)
+        gains(d); matrix(qkv, d)
+        if getattr(shape, "qk_norm", 0):                # gains of the query / key head normalisation follow wqkv
+            gains(shape.head_dim); gains(shape.head_dim)
+        matrix(d, qd); gains(d); matrix(2 * F, d); matrix(d, F)
     gains(d); matrix(V, d)
     assert at == src.size, "blob size does not match the quantised layout"
     return dataclasses.replace(shape, weight_dtype=0), np.concatenate(out)

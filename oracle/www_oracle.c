@@ -15,6 +15,9 @@
  *
  *   x  = E[token]
  *   for each layer:  u = rmsnorm(x, g1);  q,k,v = u Wq^T, u Wk^T, u Wv^T  (per head)
+ *                    [qk_norm models: q_h = rmsnorm(q_h, gq); k_j = rmsnorm(k_j, gk), over the head's hd values,
+ *                     gains gq, gk [hd] shared by the heads of the layer -- the per-head query / key
+ *                     normalisation of the Qwen3 family the paper serves (Sec. 6.3, App. C)]
  *                    q_h = rope(q_h, p); k_j = rope(k_j, p); cache (k, v) at position p
  *                    o_h = sum_i softmax_i( q_h . k_{j,i} / sqrt(hd) ) v_{j,i},  i = 0..p, j = h / G
  *                    x  += concat(o) Wo^T
@@ -49,10 +52,11 @@ typedef struct {
   float rms_eps, rope_theta;
   int32_t kv_block_size;
   int32_t weight_dtype; /* 0 = fp32, 1 = bf16 */
+  int32_t qk_norm;      /* 1: query and key heads are RMS-normalised before the rotation */
 } orc_config;
 
 typedef struct {
-  size_t attn_norm, wqkv, wo, ffn_norm, wgu, wd;
+  size_t attn_norm, wqkv, q_norm, k_norm, wo, ffn_norm, wgu, wd;
 } orc_layer_off;
 
 typedef struct orc_model {
@@ -216,6 +220,10 @@ orc_model* orc_create(const orc_config* c, const void* blob, int32_t max_seqs, i
   for (int l = 0; l < c->n_layers; ++l) {
     m->lo[l].attn_norm = off; off += align_up(d * 4);
     m->lo[l].wqkv = off;      off += align_up(qkv * d * wb);
+    if (c->qk_norm) {
+      m->lo[l].q_norm = off;  off += align_up((size_t)c->head_dim * 4);
+      m->lo[l].k_norm = off;  off += align_up((size_t)c->head_dim * 4);
+    }
     m->lo[l].wo = off;        off += align_up(d * qd * wb);
     m->lo[l].ffn_norm = off;  off += align_up(d * 4);
     m->lo[l].wgu = off;       off += align_up(2 * F * d * wb);
@@ -345,6 +353,10 @@ int orc_forward(orc_model* m, const int32_t* tokens, const int32_t* q_lens, cons
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < T; ++r) {
       float* row = qkv + r * QKV;
+      if (c->qk_norm)
+        for (int h = 0; h < Hq + Hkv; ++h)
+          orc_rmsnorm(row + (int64_t)h * hd, row + (int64_t)h * hd, (const float*)(m->blob + (h < Hq ? o->q_norm : o->k_norm)), hd,
+                      (double)c->rms_eps);
       for (int h = 0; h < Hq + Hkv; ++h) orc_rope(row + (int64_t)h * hd, row + (int64_t)h * hd, hd, row_pos[r], (double)c->rope_theta);
       int b = row_seq[r];
       if (m->kv_contig) {

@@ -128,6 +128,7 @@ class ModelShape:
     weight_dtype: int = WDTYPE_BF16
     seed: int = 0
     kv_block_size: int = KV_BLOCK
+    qk_norm: int = 0   # 1: every query and key head is RMS-normalised (own gains, shared by the heads of a layer) before the rotation
 
     @property
     def qkv_rows(self) -> int:
@@ -140,6 +141,7 @@ class ModelShape:
     def n_params(self) -> int:
         d, F, V = self.d_model, self.ffn_dim, self.vocab
         per_layer = 2 * d + self.qkv_rows * d + d * self.n_q_heads * self.head_dim + 2 * F * d + d * F
+        per_layer += 2 * self.head_dim if self.qk_norm else 0
         return 2 * V * d + d + self.n_layers * per_layer
 
 
@@ -181,6 +183,9 @@ def blob_layout(shape: ModelShape):
     for l in range(shape.n_layers):
         add(f"l{l}.attn_norm", 1, d, WDTYPE_F32)
         add(f"l{l}.wqkv", shape.qkv_rows, d, wd)
+        if shape.qk_norm:
+            add(f"l{l}.q_norm", 1, shape.head_dim, WDTYPE_F32)
+            add(f"l{l}.k_norm", 1, shape.head_dim, WDTYPE_F32)
         add(f"l{l}.wo", d, shape.n_q_heads * shape.head_dim, wd)
         add(f"l{l}.ffn_norm", 1, d, WDTYPE_F32)
         add(f"l{l}.wgu", 2 * F, d, wd)
@@ -315,6 +320,11 @@ class Workload:
 def workload(name: str) -> Workload:
     """The synthetic configurations ("tiny", "1b", "8b", "duel_1b", "duel_8b"; "1b-fp8wo" / "8b-fp8wo": the same jobs
     with the matrices stored as FP8 codes; "-int4wo128" / "-int4wo32": as 4-bit codes with group-wise scales)."""
+    if name.endswith("-qknorm"):     # the same job on a model whose query and key heads are normalised
+        import dataclasses
+        w = workload(name[:-len("-qknorm")])
+        return Workload(name, dataclasses.replace(w.shape, name=w.shape.name + "-qknorm", qk_norm=1), w.prompt_lens,
+                        w.prompt_tokens, w.decode_steps)
     for suffix, dt in (("-fp8wo", WDTYPE_FP8WO), ("-int4wo128", WDTYPE_INT4WO_128), ("-int4wo32", WDTYPE_INT4WO_32)):
         if name.endswith(suffix):
             import dataclasses

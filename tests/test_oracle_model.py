@@ -13,6 +13,7 @@ from paper_2603_20661_amd import synth
 
 SMALL = synth.ModelShape("small", 3, 64, 4, 2, 16, 96, 50, 1e-5, 1e4, synth.WDTYPE_F32, seed=11)
 SMALL_BF16 = dataclasses.replace(SMALL, weight_dtype=synth.WDTYPE_BF16, seed=12)
+SMALL_QKN = dataclasses.replace(SMALL, qk_norm=1, seed=13)       # query and key heads normalised before the rotation
 
 
 def library_forward(shape, blob, tokens):
@@ -33,7 +34,11 @@ def library_forward(shape, blob, tokens):
         u = F.rms_norm(x, (shape.d_model,), t(f"l{l}.attn_norm"), eps=shape.rms_eps)
         qkv = F.linear(u, t(f"l{l}.wqkv"))
         q, k, v = qkv.split([Hq * hd, Hkv * hd, Hkv * hd], -1)
-        q, k, v = rope(q.view(S, Hq, hd)), rope(k.view(S, Hkv, hd)), v.view(S, Hkv, hd)
+        q, k, v = q.view(S, Hq, hd), k.view(S, Hkv, hd), v.view(S, Hkv, hd)
+        if shape.qk_norm:
+            q = F.rms_norm(q, (hd,), t(f"l{l}.q_norm"), eps=shape.rms_eps)
+            k = F.rms_norm(k, (hd,), t(f"l{l}.k_norm"), eps=shape.rms_eps)
+        q, k = rope(q), rope(k)
         o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None], v.transpose(0, 1)[None],
                                            is_causal=True, enable_gqa=True)[0].transpose(0, 1).reshape(S, Hq * hd)
         x = x + F.linear(o, t(f"l{l}.wo"))
@@ -51,7 +56,7 @@ def run_prefill(shape, blob, lens, toks, permute=True, paged=True, seed=3, num_b
     return m, bt, out
 
 
-@pytest.mark.parametrize("shape", [SMALL, SMALL_BF16])
+@pytest.mark.parametrize("shape", [SMALL, SMALL_BF16, SMALL_QKN])
 def test_forward_matches_library_composition(shape):
     blob = synth.make_blob(shape, std=0.2, gain_std=0.1)            # large weights: attention is far from uniform
     lens = np.array([23, 1, 40], np.int32)
@@ -75,6 +80,32 @@ def test_tiny_config_first_token_matches_library_composition():
         ref = library_forward(wl.shape, blob, wl.prompt_tokens[b * 128:(b + 1) * 128])[-1]
         assert np.abs(logits[b] - ref).max() <= 1e-4
         assert nxt[b] == int(np.argmax(ref))
+
+
+def test_head_normalisation_forgets_the_length_of_queries_and_keys():
+    """With normalised heads, multiplying all weights of one query head and one key head by a constant changes nothing
+    (up to the epsilon under the root, 1e-5 against mean squares of order 10); without, the same change moves the logits.
+    The value heads are not normalised: scaling one of them does move the logits."""
+    lens = np.array([19, 7], np.int32)
+    toks = synth.tokens(21, int(lens.sum()), SMALL_QKN.vocab)
+    hd, Hq, Hkv = SMALL_QKN.head_dim, SMALL_QKN.n_q_heads, SMALL_QKN.n_kv_heads
+
+    def logits_with(shape, q_factor, k_factor, v_factor):
+        blob = synth.make_blob(shape, std=0.2, gain_std=0.1)
+        ent = {e[0]: e for e in synth.blob_layout(shape)[0]}
+        for l in range(shape.n_layers):
+            _, off, rows, cols, _ = ent[f"l{l}.wqkv"]
+            w = blob[off:off + 4 * rows * cols].view(np.float32).reshape(rows, cols)
+            w[1 * hd:2 * hd] *= q_factor                              # query head 1
+            w[(Hq + 1) * hd:(Hq + 2) * hd] *= k_factor                # key head 1
+            w[(Hq + Hkv) * hd:(Hq + Hkv + 1) * hd] *= v_factor        # value head 0
+        return run_prefill(shape, blob, lens, toks)[2][0]
+
+    base = logits_with(SMALL_QKN, 1.0, 1.0, 1.0)
+    np.testing.assert_allclose(logits_with(SMALL_QKN, 4.0, 0.25, 1.0), base, rtol=0, atol=2e-4)
+    assert np.abs(logits_with(SMALL_QKN, 1.0, 1.0, 4.0) - base).max() > 1e-2
+    plain = dataclasses.replace(SMALL_QKN, qk_norm=0)
+    assert np.abs(logits_with(plain, 4.0, 1.0, 1.0) - logits_with(plain, 1.0, 1.0, 1.0)).max() > 1e-2
 
 
 def test_paged_equals_contiguous_and_block_permutation_is_invisible():
