@@ -580,6 +580,7 @@ def main():
 def measured_copy_bandwidth(dev, stream):
     """What a plain device-to-device copy reaches on this GPU (read plus written bytes over the time between two events):
     the achievable figure beside the published 8 TB/s that the roofline fractions are quoted against."""
+    import torch
     nbytes = 1 << 30
     src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
@@ -601,6 +602,7 @@ def measured_copy_bandwidth(dev, stream):
 
 
 def event_pair_floor(dev, stream):
+    import torch
     busy = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
     tiny = torch.zeros(64, dtype=torch.int32, device=dev)
     with torch.cuda.stream(stream):

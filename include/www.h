@@ -32,6 +32,7 @@
  * [out_features][in_features] in `weight_dtype`, gains in fp32:
  *     embed[vocab][d]
  *     per layer: attn_norm[d], wqkv[(Hq+2Hkv)*hd][d] (q heads, then k heads, then v heads),
+ *                [WWW_FLAG_QK_NORM models: q_norm[hd], k_norm[hd],]
  *                wo[d][Hq*hd], ffn_norm[d], wgu[2F][d] (gate rows, then up rows), wd[d][F]
  *     final_norm[d], lm_head[vocab][d]
  *
@@ -76,6 +77,12 @@ extern "C" {
                               Everything else as for WWW_DTYPE_FP8WO. */
 #define WWW_DTYPE_INT4WO_32 4u  /* the same with runs of 32 columns ("int4wo-32"); the three sizes must be multiples of 32 */
 
+/* www_config.flags */
+#define WWW_FLAG_QK_NORM 1u /* every query head and every key head is RMS-normalised over its head_dim values, with the gains
+                               q_norm / k_norm of its layer (shared by the heads) and rms_eps, before the rotary embedding; the
+                               value heads are not.  This is the per-head normalisation of the Qwen3 family that the paper's
+                               nodes serve (Sec. 6.3, App. C); the paper itself gives no model equations. */
+
 typedef struct www_model www_model; /* opaque handle */
 
 /* Model shape and capacities.  Supported: head_dim in {64, 128}; d_model % 128 == 0 and <= 8192; ffn_dim % 16 == 0;
@@ -89,7 +96,7 @@ typedef struct {
   uint32_t max_batch;          /* most sequences in one call */
   uint32_t max_blocks_per_seq; /* row length of block tables; longest sequence = 16 * this */
   uint32_t max_prefill_tokens; /* most new tokens in one www_prefill call (sum of q_lens) */
-  uint32_t reserved;           /* 0 */
+  uint32_t flags;              /* WWW_FLAG_* bits, 0 for the plain decoder */
   uint64_t num_kv_blocks;      /* blocks in the KV pool */
 } www_config;
 

@@ -22,6 +22,7 @@ EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step"
            "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
            "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
            "www_get_stats", "www_sample_top_p")
+FLAG_QK_NORM = 1
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
 
@@ -30,7 +31,7 @@ class WwwConfig(ctypes.Structure):
                 ("abi_version", "n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab")] + \
                [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)] + \
                [(n, ctypes.c_uint32) for n in ("kv_block_size", "weight_dtype", "max_batch", "max_blocks_per_seq",
-                                               "max_prefill_tokens", "reserved")] + \
+                                               "max_prefill_tokens", "flags")] + \
                [("num_kv_blocks", ctypes.c_uint64)]
 
 
@@ -125,7 +126,8 @@ def make_config(shape, max_batch, max_blocks_per_seq, max_prefill_tokens, num_kv
     """shape: object with the model-shape attribute names (n_layers, d_model, ...)."""
     return WwwConfig(ABI_VERSION, shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                      shape.ffn_dim, shape.vocab, shape.rms_eps, shape.rope_theta, shape.kv_block_size, shape.weight_dtype,
-                     max_batch, max_blocks_per_seq, max_prefill_tokens, 0, num_kv_blocks)
+                     max_batch, max_blocks_per_seq, max_prefill_tokens, FLAG_QK_NORM if getattr(shape, "qk_norm", 0) else 0,
+                     num_kv_blocks)
 
 
 def www_query_sizes(cfg: WwwConfig):

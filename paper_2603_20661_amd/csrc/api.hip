@@ -80,7 +80,7 @@ static int check_config(const www_config* c) {
   else if (c->num_kv_blocks > 0x7fffffffull) why = "num_kv_blocks must fit int32";
   else if (c->max_prefill_tokens == 0) why = "max_prefill_tokens must be positive";
   else if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) why = "bad rms_eps / rope_theta";
-  else if (c->reserved != 0) why = "reserved must be 0";
+  else if (c->flags & ~WWW_FLAG_QK_NORM) why = "unknown bits in flags";
   if (!why && c->weight_dtype >= WWW_DTYPE_INT4WO_128) {
     const uint32_t g = c->weight_dtype == WWW_DTYPE_INT4WO_128 ? 128u : 32u;
     if (c->d_model % g || (c->n_q_heads * c->head_dim) % g || c->ffn_dim % g)
@@ -113,6 +113,7 @@ struct Plan {
   std::vector<uint64_t> attn_norm, ffn_norm, wqkv, wqkv_lo, wo, wo_lo, wgu, wgu_lo, wd, wd_lo;
   std::vector<uint64_t> wqkv8, wo8, wgu8, wd8;  // weight-only quantised models: packed codes for the decode path
   std::vector<uint64_t> gqkv, go, ggu, gd;      // int4: group scales for the decode path
+  std::vector<uint64_t> qk_gain;                // gains of the query / key head normalisation, in packed row order
   uint64_t lm_head8, g_lm;
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
   uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_hdr, attn_start, attn_pref;
@@ -122,7 +123,7 @@ struct Plan {
 
 struct Dims {
   int L, d, Hq, Hkv, hd, G, F, Fp, V, QKVN, QD, KD, maxB, MTmax, maxT, max_pos;
-  bool wsplit, fp8;
+  bool wsplit, fp8, qk_norm;
   int int4_group;  // 0: not an int4 source
 };
 
@@ -135,6 +136,7 @@ static Dims dims_of(const www_config* c) {
   s.max_pos = c->max_blocks_per_seq * KV_BS;
   s.wsplit = c->weight_dtype == WWW_DTYPE_F32;
   s.fp8 = c->weight_dtype == WWW_DTYPE_FP8WO;
+  s.qk_norm = (c->flags & WWW_FLAG_QK_NORM) != 0;
   s.int4_group = c->weight_dtype == WWW_DTYPE_INT4WO_128 ? 128 : c->weight_dtype == WWW_DTYPE_INT4WO_32 ? 32 : 0;
   return s;
 }
@@ -178,6 +180,7 @@ static void make_plan(const www_config* c, Plan& p) {
     p.go.push_back(s.int4_group ? take(gscale_bytes(s.d, s.QD)) : 0);
     p.ggu.push_back(s.int4_group ? take(gscale_bytes(2 * (uint64_t)s.F, s.d)) : 0);
     p.gd.push_back(s.int4_group ? take(gscale_bytes(s.d, s.Fp)) : 0);
+    p.qk_gain.push_back(s.qk_norm ? take((uint64_t)2 * s.hd * 4) : 0);
   }
   p.zero_begin = off;
   const uint64_t Mpad = (uint64_t)s.MTmax * 16;
@@ -240,7 +243,8 @@ static uint64_t blob_bytes(const www_config* c) {
   uint64_t off = align256((uint64_t)s.V * s.d * wb_embed);
   for (int l = 0; l < s.L; ++l)
     off += align256((uint64_t)s.d * 4) * 2 + blob_matrix_bytes(s, s.QKVN, s.d) + blob_matrix_bytes(s, s.d, s.QD) +
-           blob_matrix_bytes(s, 2 * (uint64_t)s.F, s.d) + blob_matrix_bytes(s, s.d, s.F);
+           blob_matrix_bytes(s, 2 * (uint64_t)s.F, s.d) + blob_matrix_bytes(s, s.d, s.F) +
+           (s.qk_norm ? 2 * align256((uint64_t)s.hd * 4) : 0);
   off += align256((uint64_t)s.d * 4) + blob_matrix_bytes(s, s.V, s.d);
   return off;
 }
@@ -327,6 +331,15 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
     LOAD_TRY(hipMemcpyAsync(ws + p.attn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);
     if (pack(s.QKVN, s.d, 1, p.wqkv[l], p.wqkv_lo[l], p.wqkv8[l], &w.sqkv, p.gqkv[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
+    if (s.qk_norm) {  // q_norm[hd], k_norm[hd]: stored in the row order of the packed heads
+      const uint64_t slot = align256((uint64_t)s.hd * 4);
+      if (launch_pack_qk_gain((const float*)(blob + src), (const float*)(blob + src + slot), s.hd, (float*)(ws + p.qk_gain[l]), st)) {
+        set_error("pack launch failed");
+        return fail(WWW_E_HIP);
+      }
+      src += 2 * slot;
+      w.qk_gain = (const float*)(ws + p.qk_gain[l]);
+    }
     if (pack(s.d, s.QD, 0, p.wo[l], p.wo_lo[l], p.wo8[l], &w.so, p.go[l])) { set_error("pack launch failed"); return fail(WWW_E_HIP); }
     LOAD_TRY(hipMemcpyAsync(ws + p.ffn_norm[l], blob + src, (uint64_t)s.d * 4, hipMemcpyDeviceToDevice, st));
     src += align256((uint64_t)s.d * 4);

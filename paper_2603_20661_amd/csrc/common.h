@@ -88,6 +88,7 @@ struct LayerW {
   float sqkv, so, sgu, sd;                  // ... FP8: the matrices' scales (1 otherwise)
   const void *gqkv, *go, *ggu, *gd;         // ... int4: group scales as fp16, [chunk of 4 k blocks][packed row][4]
   const float *attn_norm, *ffn_norm;
+  const float* qk_gain;  // models with normalised query / key heads: [2][hd] gains (q, then k) in packed row order, else null
 };
 
 struct GraphEntry {
@@ -163,6 +164,7 @@ void prof_mark(www_model* m, int cls, hipStream_t st);  // records an event in f
 void set_error(const char* fmt, ...);
 int launch_pack_int4(const void* codes, const void* scales_bf16, int N, int K, int KB, int group, int mode, int hd, int n_rot_rows, int F,
                      uint16_t* f16_plane, uint8_t* codes_out, void* scales_out, hipStream_t st);
+int launch_pack_qk_gain(const float* q_src, const float* k_src, int hd, float* out, hipStream_t st);
 int launch_pack_fp8(const void* src, int N, int K, int KB, int mode, int hd, int n_rot_rows, int F, uint8_t* out, hipStream_t st);
 int decode_attn_resident_waves(int hd, int G);
 int decode_probe_placement(int32_t* scratch_dev, int n, hipStream_t st);

@@ -100,6 +100,7 @@ struct GemmP {
   const int32_t *seq_lens, *table;
   int mbs, hd, Hq, Hkv;
   const float2* rope;
+  const float* qk_gain;  // models with normalised query / key heads: [2][hd] gains in packed row order; null otherwise
   // residual epilogue
   float* h;
   const float* gain_next;
@@ -430,6 +431,9 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
     for (int r = 0; r < R; ++r) {
       const int n0 = rgc[r] * 16 + rsub;
       if constexpr (EPI == EPI_RESID) gv_pre[r] = *reinterpret_cast<const f32x4*>(p.gain_next + n0);
+      if constexpr (EPI == EPI_QKV) {  // gains of the head normalisation (value rows read the key gains and ignore them)
+        if (p.qk_gain) gv_pre[r] = *reinterpret_cast<const f32x4*>(p.qk_gain + (n0 / p.hd < p.Hq ? 0 : p.hd) + n0 % p.hd);
+      }
 #pragma unroll
       for (int tb = 0; tb < MTK; ++tb) {
         if constexpr (EPI == EPI_RESID) hv_pre[r][tb] = *reinterpret_cast<const f32x4*>(p.h + (int64_t)tok_c[tb] * p.d + n0);
@@ -507,6 +511,37 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
 #pragma unroll
   for (int tb = 0; tb < MTK; ++tb) ssq_local[tb] = 0.f;
 
+  // Normalised query / key heads: 1 / rms of each token's head vector.  A row tile holds whole heads (128 rows: one head
+  // of 128, or two of 64 owned by wavefronts 0,1 and 2,3); a wavefront adds the squares of its 32 rows per token (lanes,
+  // then two cross-lane exchanges) and the wavefronts of a head are added through LDS in index order.  Row groups past
+  // the end of the matrix only ever fall into a head that does not exist.
+  float head_rs[MTK];
+  if constexpr (EPI == EPI_QKV) {
+    if (p.qk_gain) {
+#pragma unroll
+      for (int tb = 0; tb < MTK; ++tb) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float v = acc[r][tb][i] * scale_pre[tb];
+            s += v * v;
+          }
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (lane < 16) red[wave][tb * 16 + lane] = s;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int tb = 0; tb < MTK; ++tb) {
+        const int at = tb * 16 + tsub;
+        const float tot = p.hd == 128 ? (red[0][at] + red[1][at]) + (red[2][at] + red[3][at]) : red[wave & 2][at] + red[(wave & 2) + 1][at];
+        head_rs[tb] = rsqrtf(tot / (float)p.hd + p.eps);
+      }
+    }
+  }
+
 #pragma unroll
   for (int tb = 0; tb < MTK; ++tb) {
     const int t = (tb0 + tb) * 16 + tsub;
@@ -554,6 +589,10 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
           const int rot_rows = (p.Hq + p.Hkv) * p.hd;
           const int head = n0 / p.hd, c0 = n0 % p.hd;
           if (n0 < rot_rows) {
+            if (p.qk_gain) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[i] *= head_rs[tb] * gv_pre[r][i];
+            }
             // rows arrive with the rotary pair (i, i + hd/2) at neighbouring positions (2i, 2i+1)
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
@@ -1111,7 +1150,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
-      p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
+      p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope; p.qk_gain = w.qk_gain;
       prof_mark(m, PK_QKV, st);
       launch_gemm<EPI_QKV>(m, p, MT, st);
     }

@@ -71,6 +71,20 @@ int launch_pack_matrix(const void* src, int src_dtype, int N, int K, int KB, int
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// Gains of the query / key head normalisation, [2][hd], in the row order of a packed head (rotary pairs adjacent).
+__global__ void pack_qk_gain_kernel(const float* __restrict__ q_src, const float* __restrict__ k_src, int hd, float* __restrict__ out) {
+  const int p = threadIdx.x;
+  if (p >= hd) return;
+  const int s = source_row(p, 1, hd, hd, 0);
+  out[p] = q_src[s];
+  out[hd + p] = k_src[s];
+}
+
+int launch_pack_qk_gain(const float* q_src, const float* k_src, int hd, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(pack_qk_gain_kernel, dim3(1), dim3(128), 0, st, q_src, k_src, hd, out);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 // FP8 codes in the order the decode GEMM streams them: 16-byte unit ((pair of k blocks j, row group rg), lane) holds the
 // lane's 8 codes of k block 2j followed by its 8 codes of k block 2j + 1 (rows and k positions as in the fp16 layout);
 // positions past K, and the second half of a last odd block, are zero codes.

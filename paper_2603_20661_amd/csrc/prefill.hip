@@ -101,6 +101,7 @@ struct PGemmP {
   int T;
   int n_tt, n_rt;  // token tiles, row tiles
   // QKV epilogue
+  const float* qk_gain;  // models with normalised query / key heads: [2][hd] gains in packed row order; null otherwise
   uint16_t* qp;
   uint16_t *kplane, *vplane;
   const int32_t *row_seq, *row_pos, *table;
@@ -329,7 +330,19 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
       }
     }
   }
-  f32x4 gv[4][4];  // next norm's gain for this lane's 16 x 4 rows (residual epilogue)
+  f32x4 gv[4][4];  // next norm's gain for this lane's 16 x 4 rows (residual epilogue); gains of the head normalisation (QKV)
+  if constexpr (EPI == PEPI_QKV) {
+    if (p.qk_gain) {
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
+          const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
+          gv[rb][q4] = *reinterpret_cast<const f32x4*>(p.qk_gain + (n0 / p.hd < p.Hq ? 0 : p.hd) + n0 % p.hd);  // (value rows: unused)
+        }
+    }
+  }
   if constexpr (EPI == PEPI_RESID) {
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb)
@@ -361,6 +374,28 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         }
     }
     float ssq_tok = 0.f;
+    // Normalised query / key heads: a wavefront's 128 rows are one head of 128 or two heads of 64 (row blocks 0,1 and
+    // 2,3), and a token's values of these rows sit in the two lanes l, l + 32: 1 / rms per head from the lane's own
+    // squares and one cross-lane exchange.
+    float head_rs[2] = {1.f, 1.f};
+    if constexpr (EPI == PEPI_QKV) {
+      if (p.qk_gain) {
+        float ss[2] = {0.f, 0.f};
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float v = acc[rb][tb][i] * scale[tb];
+            ss[rb >> 1] += v * v;
+          }
+        if (p.hd == 128) ss[0] = ss[1] = ss[0] + ss[1];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          ss[hh] += __shfl_xor(ss[hh], 32);
+          head_rs[hh] = rsqrtf(ss[hh] / (float)p.hd + p.eps);
+        }
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
@@ -402,6 +437,10 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
             const int rot_rows = (p.Hq + p.Hkv) * p.hd;
             const int head = n0 / p.hd, c0 = n0 % p.hd;
             if (n0 < rot_rows) {
+              if (p.qk_gain) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v4[i] *= head_rs[rb >> 1] * gv[rb][q4][i];
+              }
               const f32x4 cs = pre[rb][q4];  // (cos, sin) of the two rotary pairs held here
 #pragma unroll
               for (int pr = 0; pr < 2; ++pr) {
@@ -726,7 +765,7 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
       p.W = (const u32x4*)w.wqkv; p.wfactor = w.sqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
       p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
-      p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope;
+      p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope; p.qk_gain = w.qk_gain;
       launch_pgemm<PEPI_QKV>(p, st);
     }
     if (l == m->L - 1) break;  // only this layer's keys and values are still needed

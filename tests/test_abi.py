@@ -33,7 +33,7 @@ def test_query_sizes_and_config_validation():
     assert wsbytes > synth.M8B.n_params() * 2 - synth.M8B.vocab * synth.M8B.d_model * 2
     for field, value, code in (("abi_version", 99, B.E_ABI_MISMATCH), ("head_dim", 96, B.E_BAD_CONFIG),
                                ("kv_block_size", 32, B.E_BAD_CONFIG), ("n_kv_heads", 3, B.E_BAD_CONFIG),
-                               ("vocab", 1001, B.E_BAD_CONFIG), ("max_batch", 0, B.E_BAD_CONFIG), ("reserved", 1, B.E_BAD_CONFIG)):
+                               ("vocab", 1001, B.E_BAD_CONFIG), ("max_batch", 0, B.E_BAD_CONFIG), ("flags", 2, B.E_BAD_CONFIG)):
         bad = B.make_config(synth.TINY, 4, 16, 512, 64)
         setattr(bad, field, value)
         with pytest.raises(B.WwwError) as e:

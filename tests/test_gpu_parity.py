@@ -161,6 +161,45 @@ def test_full_width_layers_at_bench_batch(shape, batch):
     check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
 
 
+# ------------------------------------------------------------------ models with normalised query / key heads
+MID64_QKN = dataclasses.replace(MID64, name="mid64qkn", qk_norm=1, seed=41)
+MID128_QKN = dataclasses.replace(MID128, name="mid128qkn", qk_norm=1, seed=42)
+MIDF32_QKN = dataclasses.replace(MIDF32, name="midf32qkn", qk_norm=1, seed=43)
+# one query head and one kv head of 64: 192 rows of wqkv, so the last 128-row tile of the decode GEMM and the only
+# 256-row tile of the prefill GEMM end in the middle (the missing heads' sums must not leak into real ones)
+ODD64_QKN = synth.ModelShape("odd64qkn", 2, 256, 1, 1, 64, 352, 512, 1e-5, 1e4, synth.WDTYPE_BF16, seed=44, qk_norm=1)
+WIDE8B_QKN = dataclasses.replace(WIDE8B, name="wide8bqkn", qk_norm=1, seed=45)
+WIDE1B_QKN = dataclasses.replace(WIDE1B, name="wide1bqkn", qk_norm=1, seed=46)
+
+
+@pytest.mark.parametrize("shape,lens,steps,chunk", [
+    (MID64_QKN, [70, 1, 16, 300, 33], 5, None),
+    (MID128_QKN, [129, 17, 64, 5, 260, 31, 2], 4, 48),
+    (MIDF32_QKN, [40, 90], 4, None),
+    (ODD64_QKN, [50, 3, 270], 4, None),
+    (dataclasses.replace(MID128_QKN, name="mid128qknfp8", weight_dtype=synth.WDTYPE_FP8WO), [129, 17, 64, 5], 4, None),
+    (synth.ModelShape("q32hd64qkn", 2, 256, 8, 4, 64, 736, 1024, 1e-5, 1e4, synth.WDTYPE_INT4WO_32, seed=47, qk_norm=1), [129, 17, 64, 5], 4, None),
+])
+def test_models_with_normalised_query_and_key_heads(shape, lens, steps, chunk):
+    """per-head RMS normalisation of q and k in front of the rotation, in the QKV epilogues of both GEMMs (gains drawn
+    around 1 with spread 0.1, so a gain applied to the wrong row of a rotary pair shows)"""
+    check(run_job(shape, lens, steps, seed=90, chunk=chunk), f"{shape.name}")
+
+
+def test_normalised_heads_across_token_group_boundaries():
+    lens = 3 + synth.uniform_i32(33, 9, 33, 40)
+    check(run_job(MID64_QKN, lens, 3, seed=91), "mid64qkn batch 33")
+
+
+@pytest.mark.parametrize("shape,batch", [(WIDE8B_QKN, 64), (WIDE1B_QKN, 32)])
+def test_normalised_heads_full_width_layers(shape, batch):
+    """the 8B- and 1B-wide matrices with the benchmark's tiles and split-K factors (the head sums cross the four
+    wavefronts of the workgroup that finishes a split row tile)"""
+    lens = 1 + synth.uniform_i32(batch, 11, batch, 40)
+    lens[0], lens[1] = 1, 16
+    check(run_job(shape, lens, 3, seed=92, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+
+
 # ------------------------------------------------------------------ fp8 weight-only models
 MID128_FP8 = dataclasses.replace(MID128, name="mid128fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=24)
 MID64_FP8 = dataclasses.replace(MID64, name="mid64fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=25)
