@@ -424,7 +424,7 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="8b", choices=["tiny", "1b", "8b", "duel", "mixed", "1b-fp8wo", "8b-fp8wo", "1b-int4wo128", "8b-int4wo128",
-                                                          "1b-int4wo32", "8b-int4wo32"])
+                                                          "1b-int4wo32", "8b-int4wo32", "1b-qknorm", "8b-qknorm"])
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
