@@ -30,6 +30,13 @@ def test_query_sizes_and_config_validation():
     wbytes, kvbytes, wsbytes = B.www_query_sizes(cfg)
     assert wbytes == synth.blob_layout(synth.M8B)[1]
     assert kvbytes == 6000 * 32 * 2 * 8 * 16 * 128 * 2          # 2 MiB per block for the 8B shape
+    # the blob of every source format, with and without the gains of the head normalisation, is as long as the generator's
+    import dataclasses
+    for base in (synth.M8B, synth.M1B, synth.TINY):
+        for wd in ((base.weight_dtype,) if base is synth.TINY else (1, 2, 3, 4)):
+            for qkn in (0, 1):
+                shape = dataclasses.replace(base, weight_dtype=wd, qk_norm=qkn)
+                assert B.www_query_sizes(B.make_config(shape, 4, 16, 512, 64))[0] == synth.blob_layout(shape)[1], shape
     assert wsbytes > synth.M8B.n_params() * 2 - synth.M8B.vocab * synth.M8B.d_model * 2
     for field, value, code in (("abi_version", 99, B.E_ABI_MISMATCH), ("head_dim", 96, B.E_BAD_CONFIG),
                                ("kv_block_size", 32, B.E_BAD_CONFIG), ("n_kv_heads", 3, B.E_BAD_CONFIG),
