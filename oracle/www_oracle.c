@@ -138,6 +138,7 @@ static void softmax_f64(double* p, const double* s, int64_t n) {
 }
 
 void orc_softmax(float* p, const float* s, int64_t n) {
+  if (n <= 0) return; /* nothing to normalise */
   double* a = (double*)malloc(sizeof(double) * (size_t)n * 2);
   for (int64_t i = 0; i < n; ++i) a[i] = (double)s[i];
   softmax_f64(a + n, a, n);
