@@ -9,7 +9,10 @@ a HIP graph, tokens fed back on the device).  Prints ONE JSON line:
   prefill_tokens_per_s prompt tokens per second of the prefill calls in the same steps
   roofline            dominant decode kernel: algorithmic HBM bytes per launch / its mean duration
                       (HIP events around every kernel of extra, untimed, eagerly launched steps)
+                      (event_pair_floor_ms: what an event pair around a near-empty kernel reads in a busy stream)
   roofline_decode_step / roofline_prefill   whole-phase figures from the timed region
+  measured_copy_bandwidth   read + written bytes per second of a plain 1 GiB device copy on the same stream: the achievable
+                      figure beside the published peak (roofline_decode_step.frac_of_measured_copy relates the step to it)
   cpu_baseline        the CPU oracle timed on a bounded sample of the same decode workload
 
 Two composite workloads print the same kind of line with their own phases:
@@ -25,6 +28,7 @@ Two composite workloads print the same kind of line with their own phases:
   --workload 8b-fp8wo / 1b-fp8wo   the 8B / 1B jobs with the matrices stored as FP8 E4M3 codes (weight-only; arithmetic
                      and activations unchanged); rooflines count one byte per streamed weight
   --workload 8b-int4wo128 / 8b-int4wo32 / 1b-...   the same with 4-bit codes and a bf16 scale per group of 128 / 32
+  --workload 8b-qknorm / 1b-qknorm   the same jobs on a model whose query and key heads are RMS-normalised before the rotation
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1b|tiny|duel|mixed|8b-fp8wo|8b-int4wo128|...]
 """
