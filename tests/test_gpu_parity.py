@@ -362,13 +362,13 @@ def test_capacity_and_argument_errors_on_device():
         sess.close()
 
 
-@pytest.mark.parametrize("name", ["8b", "1b"])
+@pytest.mark.parametrize("name", ["8b", "1b", "8b-qknorm", "1b-qknorm"])
 def test_bench_configuration_sampled_against_oracle(name):
     """The 8B- and 1B-shaped workloads exactly as bench.py launches them (8B: batch 64, 80 231 prompt tokens in one
     prefill call; 1B: batch 32, about 40 000 prompt tokens; then decode steps), at full depth.  Properties at full size:
     logits finite although the pool starts as NaN, bit-identical under a different physical block placement.  Sampled
     parity: the shortest sequence is recomputed alone by the oracle (prefill + 2 decode steps) and compared with its rows
-    of the batched GPU run."""
+    of the batched GPU run.  The "-qknorm" names are the same jobs on models with normalised query and key heads."""
     from oracle import oracle as O
     wl = synth.workload(name)
     shape, lens, toks = wl.shape, wl.prompt_lens.astype(np.int32), wl.prompt_tokens
