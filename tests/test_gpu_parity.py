@@ -200,6 +200,22 @@ def test_normalised_heads_full_width_layers(shape, batch):
     check(run_job(shape, lens, 3, seed=92, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
 
 
+# ------------------------------------------------------------------ the largest sizes a configuration may name
+def test_widest_model_the_configuration_allows():
+    """d_model 8192, the documented maximum: every one of the 64 entries per token of the decode path's sum-of-squares
+    table and of the 32 of the prefill path's is in use, and the QKV matrix has 80 row tiles of 128"""
+    shape = synth.ModelShape("max8192", 2, 8192, 64, 8, 128, 2048, 1024, 1e-5, 5e5, synth.WDTYPE_BF16, seed=51)
+    lens = 1 + synth.uniform_i32(51, 11, 40, 30)
+    lens[0], lens[1] = 300, 1
+    check(run_job(shape, lens, 2, seed=93, gain_std=0.05), "d_model 8192", strict=True)
+
+
+def test_largest_batch_the_configuration_allows():
+    """1024 sequences in one prefill call and in every decode step (16 groups of 64 tokens per decode GEMM)"""
+    lens = 1 + synth.uniform_i32(52, 11, 1024, 20)
+    check(run_job(MID64, lens, 2, seed=94), "batch 1024", strict=True)
+
+
 # ------------------------------------------------------------------ fp8 weight-only models
 MID128_FP8 = dataclasses.replace(MID128, name="mid128fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=24)
 MID64_FP8 = dataclasses.replace(MID64, name="mid64fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=25)
