@@ -29,8 +29,15 @@ __device__ __forceinline__ f32x4 load_shared_f32x4(__amdgpu_buffer_rsrc_t r, uin
 }
 __device__ __forceinline__ void store_shared_f32(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float load_shared_f32(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-// all of this wavefront's earlier memory operations have completed
-__device__ __forceinline__ void wait_own_memory_ops() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// All of this wavefront's earlier vector memory operations have completed (stores: acknowledged by L2).  Written as the
+// wait itself: a workgroup-scope release fence compiles to no vector-memory wait here (the wavefronts of a workgroup
+// share one L1, so for ordering inside the workgroup none is needed), and then the partial-tile stores of a slow
+// wavefront could still be on their way when the arrival counter moved: once in some ten thousand launches the last
+// workgroup read the previous launch's values of a few cache lines.
+__device__ __forceinline__ void wait_own_memory_ops() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+}
 
 // offset (in elements) of column k of token t in a packed activation buffer with MT token groups
 __device__ __forceinline__ int64_t packed_x_offset(int k, int t, int MT, int hl) {

@@ -33,6 +33,11 @@ def summarize(what, gpu_logits, gpu_next, ref_logits):
     err = float(np.abs(gpu_logits - ref_logits).max())
     agree = float((ref_logits.argmax(-1) == gpu_next).mean())
     print(f"{what}: max|dlogit|={err:.3e} agreement={agree:.4f} samples={len(gpu_next)}", flush=True)
+    if err > TOL:   # where along the sequence: one step or everything from some step on
+        per_row = np.abs(gpu_logits - ref_logits).max(-1)
+        over = np.nonzero(per_row > TOL)[0]
+        print(f"{what}: rows above tolerance {over[:20].tolist()} of {len(per_row)} (first {int(over[0])}, last {int(over[-1])}, "
+              f"count {len(over)}); row errors around the first: {np.round(per_row[max(0, over[0] - 2):over[0] + 4], 4).tolist()}", flush=True)
     return err, agree
 
 

@@ -200,6 +200,43 @@ def test_normalised_heads_full_width_layers(shape, batch):
     check(run_job(shape, lens, 3, seed=92, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
 
 
+def test_results_do_not_depend_on_what_device_memory_held_before():
+    """GPU vs GPU: the same job over memory that was filled with zeros, with ones (fp16 1.0 / fp32 0.0078) and with NaN
+    patterns before the library got it (workspace, KV pool and blob buffer are carved out of the poisoned block) gives
+    bit-identical logits: nothing reads a byte that the library or the caller has not written."""
+    import torch
+    shape = MID128
+    blob = synth.make_blob(shape, gain_std=0.1)
+    lens = np.array([150, 40, 9, 257], np.int32)
+    steps = 3
+    cap = lens + steps + 1
+    mbs = int((cap.max() + 15) // 16)
+    nb = int(((cap + 15) // 16).sum()) + 5
+    toks = synth.tokens(71, int(lens.sum()), shape.vocab)
+    table = synth.block_tables(71, cap, nb, mbs, permute=True)
+    runs = []
+    for pattern in (0, 0x3C00, 0x7FC0):
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        junk = torch.empty(1 << 29, dtype=torch.int16, device="cuda:0")     # 1 GiB, far more than the session needs
+        junk.fill_(pattern)
+        torch.cuda.synchronize()
+        del junk                                                           # stays in the allocator's cache: the session reuses it
+        sess = GpuSession(shape, blob, len(lens), mbs * 16, int(lens.sum()), nb, kv_poison=False)
+        try:
+            lg, nx = sess.prefill(toks, lens, lens, table)
+            out, cur = [lg], lens.copy()
+            for _ in range(steps):
+                cur = cur + 1
+                lg, nx = sess.decode(nx, cur, table)
+                out.append(lg)
+            runs.append(np.stack(out))
+        finally:
+            sess.close()
+    assert np.isfinite(runs[0]).all()
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0].view(np.uint32), runs[2].view(np.uint32))
+
+
 # ------------------------------------------------------------------ the largest sizes a configuration may name
 def test_widest_model_the_configuration_allows():
     """d_model 8192, the documented maximum: every one of the 64 entries per token of the decode path's sum-of-squares
