@@ -122,7 +122,9 @@ struct PGemmP {
   int Fp;
 };
 
-template <int EPI>
+// QKN: the QKV epilogue also normalises the query and key heads (an instantiation of its own, so that the plain model's
+// kernel carries none of its registers)
+template <int EPI, bool QKN = false>
 __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
   // three stage buffers of 2048 sixteen-byte units: 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
   extern __shared__ u32x4 smem[];
@@ -331,17 +333,15 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     }
   }
   f32x4 gv[4][4];  // next norm's gain for this lane's 16 x 4 rows (residual epilogue); gains of the head normalisation (QKV)
-  if constexpr (EPI == PEPI_QKV) {
-    if (p.qk_gain) {
+  if constexpr (EPI == PEPI_QKV && QKN) {
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
-          const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
-          gv[rb][q4] = *reinterpret_cast<const f32x4*>(p.qk_gain + (n0 / p.hd < p.Hq ? 0 : p.hd) + n0 % p.hd);  // (value rows: unused)
-        }
-    }
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
+        const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
+        gv[rb][q4] = *reinterpret_cast<const f32x4*>(p.qk_gain + (n0 / p.hd < p.Hq ? 0 : p.hd) + n0 % p.hd);  // (value rows: unused)
+      }
   }
   if constexpr (EPI == PEPI_RESID) {
 #pragma unroll
@@ -378,22 +378,20 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
     // 2,3), and a token's values of these rows sit in the two lanes l, l + 32: 1 / rms per head from the lane's own
     // squares and one cross-lane exchange.
     float head_rs[2] = {1.f, 1.f};
-    if constexpr (EPI == PEPI_QKV) {
-      if (p.qk_gain) {
-        float ss[2] = {0.f, 0.f};
+    if constexpr (EPI == PEPI_QKV && QKN) {
+      float ss[2] = {0.f, 0.f};
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+      for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float v = acc[rb][tb][i] * scale[tb];
-            ss[rb >> 1] += v * v;
-          }
-        if (p.hd == 128) ss[0] = ss[1] = ss[0] + ss[1];
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          ss[hh] += __shfl_xor(ss[hh], 32);
-          head_rs[hh] = rsqrtf(ss[hh] / (float)p.hd + p.eps);
+        for (int i = 0; i < 16; ++i) {
+          const float v = acc[rb][tb][i] * scale[tb];
+          ss[rb >> 1] += v * v;
         }
+      if (p.hd == 128) ss[0] = ss[1] = ss[0] + ss[1];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        ss[hh] += __shfl_xor(ss[hh], 32);
+        head_rs[hh] = rsqrtf(ss[hh] / (float)p.hd + p.eps);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -437,7 +435,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
             const int rot_rows = (p.Hq + p.Hkv) * p.hd;
             const int head = n0 / p.hd, c0 = n0 % p.hd;
             if (n0 < rot_rows) {
-              if (p.qk_gain) {
+              if constexpr (QKN) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v4[i] *= head_rs[rb >> 1] * gv[rb][q4][i];
               }
@@ -710,17 +708,21 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
 // ------------------------------------------------------------------------------------------------
 // Host side
 
-template <int EPI>
+template <int EPI, bool QKN = false>
 static void launch_pgemm(PGemmP& p, hipStream_t st) {
+  if constexpr (EPI == PEPI_QKV && !QKN) {
+    if (p.qk_gain) return launch_pgemm<EPI, true>(p, st);
+  }
   p.n_tt = (p.T + 255) / 256;
   p.n_rt = (p.NRG + 15) / 16;
   if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
   static bool lds_enabled = false;  // per instantiation: allow 96 KiB of dynamic LDS
   if (!lds_enabled) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, PGEMM_LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<EPI, QKN>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              PGEMM_LDS_BYTES);
     lds_enabled = true;
   }
-  hipLaunchKernelGGL(prefill_gemm_kernel<EPI>, dim3(p.n_tt * p.n_rt), dim3(256), PGEMM_LDS_BYTES, st, p);
+  hipLaunchKernelGGL((prefill_gemm_kernel<EPI, QKN>), dim3(p.n_tt * p.n_rt), dim3(256), PGEMM_LDS_BYTES, st, p);
 }
 
 template <int HD>
