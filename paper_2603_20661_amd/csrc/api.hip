@@ -214,8 +214,8 @@ static void make_plan(const www_config* c, Plan& p) {
   p.attn_pref = take(((uint64_t)s.maxB + 1) * 4);
   p.argmax_val = take((uint64_t)s.maxB * 32 * 4);
   p.argmax_idx = take((uint64_t)s.maxB * 32 * 4);
-  p.hp = take((uint64_t)s.maxT * s.d * 4);
   const uint64_t Tpad = ((uint64_t)s.maxT + 255) / 256 * 256;  // packed activation buffers hold whole 256-token tiles
+  p.hp = take(Tpad * (((uint64_t)s.d + 255) / 256 * 256) * 4);  // residual stream in whole 256 x 256 blocks (accumulator order)
   p.ssq_p = take(Tpad * (uint64_t)PSSQ * 4);
   p.xn = take(Tpad * s.d * 2);
   p.qp = take((uint64_t)s.maxT * s.QD * 2);

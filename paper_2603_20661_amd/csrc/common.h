@@ -134,7 +134,7 @@ struct www_model {
   float* logits_buf;  // used when the caller passes no logits buffer
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
   // prefill-path buffers
-  float* hp;       // [maxT][d]
+  float* hp;       // residual stream of the prefill path in 256 x 256 blocks of accumulator order (see prefill.hip)
   float* ssq_p;    // [d/256][maxT rounded to 256] partial sums of squares of hp
   uint16_t* xn;        // packed [maxT][d] normalised activations
   uint16_t* qp;    // [maxT][QD] rotated queries, fp16 (interleaved head-dim order)

@@ -53,6 +53,24 @@ __global__ __launch_bounds__(1024) void prefill_meta_kernel(const int32_t* __res
   }
 }
 
+// The residual stream of the prefill path is only ever touched by the embedding kernel and by the residual epilogues of
+// the O and down projections, which both tile it 256 tokens x 256 rows with the same accumulator layout.  It is
+// therefore kept in that layout ("register image"): block (token tile tt, row tile rt) holds 64 Ki floats ordered
+// [wavefront wn*2+wt][rb][tb][q4][lane][4], element = the lane's four consecutive rows
+//   row   = rt*256 + wn*128 + rb*32 + q4*8 + (lane/32)*4 + e,   token = tt*256 + wt*128 + tb*32 + lane%32,
+// so that every load and store of an epilogue is one contiguous KiB per wavefront instead of 64 pieces of 16 bytes
+// that lie a whole token row apart.
+__device__ __forceinline__ int64_t hp_image_offset(int tt, int rt, int n_rt, int wave, int rb, int tb, int q4, int lane) {
+  return (((((((int64_t)tt * n_rt + rt) * 4 + wave) * 4 + rb) * 4 + tb) * 4 + q4) * 64 + lane) * 4;
+}
+// the same for token t and row n (a multiple of 4)
+__device__ __forceinline__ int64_t hp_image_offset_of(int64_t t, int n, int n_rt) {
+  const int w256 = (int)(t & 255), c = n & 255;
+  const int wave = (c >> 7) * 2 + (w256 >> 7), rb = (c & 127) >> 5, tb = (w256 & 127) >> 5, q4 = (c & 31) >> 3;
+  const int lane = ((c & 7) >> 2) * 32 + (w256 & 31);
+  return hp_image_offset((int)(t >> 8), n >> 8, n_rt, wave, rb, tb, q4, lane);
+}
+
 // Embedding rows: residual stream h = E[token] (fp32), the first GEMM operand fp16(h * gain) in the packed prefill
 // layout, and the row's sum of squares.  RMSNorm's 1/rms factor is applied by the consuming GEMM's epilogue.
 template <typename ET>
@@ -72,7 +90,7 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
       local += x[e] * x[e];
       o.s[e] = f32_to_f16_sat(x[e] * gain[k + e]);
     }
-    *reinterpret_cast<float4*>(hp + r * d + k) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<float4*>(hp + hp_image_offset_of(r, k, (d + 255) >> 8)) = make_float4(x[0], x[1], x[2], x[3]);
     *reinterpret_cast<u32x2*>(xn + packed_p_offset(r, k, d >> 4)) = o.v;
   }
   __shared__ float red[256];
@@ -369,7 +387,8 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         for (int q4 = 0; q4 < 4; ++q4) {
           const int rg = min(rg_tile + wn * 8 + rb * 2 + (q4 >> 1), p.NRG - 1);
           const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
-          if constexpr (EPI == PEPI_RESID) pre[rb][q4] = *reinterpret_cast<const f32x4*>(p.hp + (int64_t)t * p.d + n0);
+          if constexpr (EPI == PEPI_RESID)  // (whole tiles are allocated: in bounds also for tokens and rows past the end)
+            pre[rb][q4] = *reinterpret_cast<const f32x4*>(p.hp + hp_image_offset(tt, rt, p.n_rt, wave, rb, tb, q4, lane));
           else pre[rb][q4] = *reinterpret_cast<const f32x4*>(p.rope + (int64_t)pos[tb] * (p.hd / 2) + ((n0 % p.hd) >> 1));
         }
     }
@@ -423,7 +442,7 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
           if constexpr (EPI == PEPI_RESID) {
             const f32x4 hv = pre[rb][q4], g4 = gv[rb][q4];
             const float hn[4] = {hv[0] + v4[0], hv[1] + v4[1], hv[2] + v4[2], hv[3] + v4[3]};
-            *reinterpret_cast<float4*>(p.hp + (int64_t)t * p.d + n0) = make_float4(hn[0], hn[1], hn[2], hn[3]);
+            *reinterpret_cast<float4*>(p.hp + hp_image_offset(tt, rt, p.n_rt, wave, rb, tb, q4, lane)) = make_float4(hn[0], hn[1], hn[2], hn[3]);
             union { uint16_t s[4]; u32x2 v; } o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
