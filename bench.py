@@ -295,6 +295,28 @@ def mixed_schedule(lens, n_seq, chunk, budget, dec_steps):
     return calls
 
 
+def time_scheduler(B, lens, n_seq, chunk, budget, dec_steps, mbs, n_calls):
+    """Host cost of the library's continuous-batching scheduler on the same request set (all requests queued at the start,
+    the whole pool usable): it plans the very schedule that is timed above, one plan + commit per iteration."""
+    need = int(((lens + dec_steps + 15) // 16).sum())
+    s = B.Scheduler(n_seq, mbs, budget, chunk, need, 1.0)
+    for b in range(n_seq):
+        s.submit(b, int(lens[b]), dec_steps + 1)
+    t0 = time.perf_counter()
+    iterations = planned_calls = 0
+    while True:
+        pre, dec = s.plan()
+        planned_calls += (1 if pre else 0) + (1 if dec else 0)
+        s.commit()
+        iterations += 1
+        if s.stats()["active"] == 0:
+            break
+    dt = time.perf_counter() - t0
+    s.close()
+    return {"iterations": iterations, "calls_planned": planned_calls, "equals_timed_schedule": planned_calls == n_calls,
+            "host_us_per_iteration": round(dt / iterations * 1e6, 1), "what": "www_sched_plan + www_sched_commit + www_get_stats through the binding"}
+
+
 def bench_mixed(args):
     """Long-context mixed batch: chunked prefill interleaved with decode steps on the 8B-shaped model."""
     import torch
@@ -417,7 +439,8 @@ def bench_mixed(args):
                                     f"{int(lens.min())}..{int(lens.max())} (sum {int(lens.sum())}), {chunk}-token prefill chunks within {budget} "
                                     f"tokens per call interleaved with decode steps, {dec_steps} greedy tokens per sequence, KV pool "
                                     f"{nb} blocks = {nb * block_bytes / 2**30:.0f} GiB with permuted block tables"))
-    out.update({"call_classes": classes, "kv_pool_GiB": round(nb * block_bytes / 2**30, 1), "checksum_last_tokens": checksum})
+    out.update({"call_classes": classes, "kv_pool_GiB": round(nb * block_bytes / 2**30, 1), "checksum_last_tokens": checksum,
+                "scheduler": time_scheduler(B, lens, n_seq, chunk, budget, dec_steps, mbs, len(calls))})
     print(json.dumps(out), flush=True)
     model.close()
 
