@@ -69,6 +69,22 @@ def test_blob_decoder_matches_tensor_by_tensor_decode():
     assert np.array_equal(emb, synth.bf16_bits_to_f32(blob[:2 * T8.vocab * T8.d_model].view(np.uint16)).reshape(T8.vocab, T8.d_model))
 
 
+@pytest.mark.parametrize("wd", [synth.WDTYPE_FP8WO, synth.WDTYPE_INT4WO_32])
+def test_blob_decoder_carries_the_head_normalisation_gains(wd):
+    """a weight-only quantised model with normalised query / key heads: the two gain vectors that follow wqkv arrive
+    unchanged at their place in the decoded blob, and so does everything behind them"""
+    shape = synth.ModelShape("t8qkn", 2, 64, 4, 2, 32, 96, 48, 1e-5, 1e4, wd, seed=53, qk_norm=1)
+    blob = synth.make_blob(shape, gain_std=0.1)
+    by_name = {e[0]: e for e in synth.blob_layout(shape)[0]}
+    shape32, blob32 = Q.dequantize_blob(shape, blob)
+    assert shape32.qk_norm == 1 and blob32.size == synth.blob_layout(shape32)[1]
+    for name, n in (("l0.q_norm", shape.head_dim), ("l1.k_norm", shape.head_dim), ("l1.ffn_norm", shape.d_model), ("final_norm", shape.d_model)):
+        src = blob[by_name[name][1]:][:4 * n].view(np.float32)
+        assert np.array_equal(synth.blob_tensor(shape32, blob32, name), src) and src.std() > 0.05
+    plain32 = Q.dequantize_blob(dataclasses.replace(shape, qk_norm=0), synth.make_blob(dataclasses.replace(shape, qk_norm=0), gain_std=0.1))[1]
+    assert blob32.size == plain32.size + 2 * shape.n_layers * 256          # two 256-byte slots per layer more than the plain model
+
+
 T4 = {g: synth.ModelShape(f"t4g{g}", 2, 128, 4, 2, 32, 256, 48, 1e-5, 1e4, dt, seed=52)
       for g, dt in ((128, synth.WDTYPE_INT4WO_128), (32, synth.WDTYPE_INT4WO_32))}
 
