@@ -13,10 +13,10 @@
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 // Cross-workgroup hand-over of partial results inside one kernel.  Partial tiles are written and read with
-// device-scope (sc1) 16-byte accesses; the producer waits for its stores, the workgroup syncs, one thread issues a
-// device-scope release fence and bumps a device-scope counter; the workgroup that sees the last count reads the
-// tiles back.  Only that one thread per workgroup fences: a device-scope fence in every wavefront (write-back plus
-// invalidate of the whole L2) costs tens of microseconds per kernel here.
+// device-scope (sc1) 16-byte accesses; every wavefront of the producer waits for its stores, the workgroup syncs, one
+// thread bumps a device-scope counter (after a device-scope release fence when the splits of a tile are not known to
+// share an L2); the workgroup that sees the last count reads the tiles back.  Only that one thread per workgroup
+// fences: a device-scope fence in every wavefront (write-back of the whole L2) costs tens of microseconds per kernel.
 // 16-byte accesses with device scope (cache-policy bit 4 = sc1 on gfx942/gfx950) through a raw buffer descriptor
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t shared_rsrc(const void* base) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
@@ -466,10 +466,9 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
     wait_own_memory_ops();
     __syncthreads();
     if (tid == 0) {
-      // Partial tiles that have to cross to another XCD need a device-scope release (L2 write-back) before the
-      // counter moves: without it a last workgroup behind another L2 now and then read a few stale cache lines of
-      // a partial tile, although the stores are write-through and had been waited for.  The barrier above orders
-      // every wavefront's completed stores before this thread's fence.
+      // Conservative path for partial tiles that may have to cross to another XCD: a device-scope release (L2
+      // write-back) before the counter moves.  The barrier above orders every wavefront's completed stores before
+      // this thread's fence.
       if (p.fence_handover) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
       // the counter also records on which XCD each split ran, so that the last workgroup can tell whether the
       // placement rule held for this tile (the unfenced hand-over is only sound if it did)
