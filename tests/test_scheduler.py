@@ -98,6 +98,17 @@ def test_equals_the_fixed_schedule_of_the_mixed_batch():
     assert mine == ref
 
 
+def test_benchmark_drives_the_library_scheduler_over_the_timed_schedule():
+    """bench.py's host-cost figure comes from the library's scheduler planning exactly the calls that were timed"""
+    n_seq, chunk, budget, dec_steps = 24, 64, 512, 5
+    lens = synth.lengths_zipf(3, n_seq, 1.2, 20, 900).astype(np.int64)
+    calls = bench.mixed_schedule(lens, n_seq, chunk, budget, dec_steps)
+    mbs = int((lens.max() + dec_steps + 1 + 15) // 16)
+    r = bench.time_scheduler(B, lens, n_seq, chunk, budget, dec_steps, mbs, len(calls))
+    assert r["equals_timed_schedule"] and r["calls_planned"] == len(calls) and r["iterations"] >= dec_steps
+    assert r["host_us_per_iteration"] > 0
+
+
 @pytest.mark.parametrize("seed,arrivals", [(11, 1), (12, 4), (13, 50)])
 def test_library_scheduler_equals_oracle_plan_by_plan(seed, arrivals):
     cfg = dict(max_batch=7, max_blocks_per_seq=30, token_budget=128, chunk_tokens=48, num_kv_blocks=120, target_utilisation=0.7)
