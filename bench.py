@@ -9,7 +9,8 @@ a HIP graph, tokens fed back on the device).  Prints ONE JSON line:
   prefill_tokens_per_s prompt tokens per second of the prefill calls in the same steps
   roofline            dominant decode kernel: algorithmic HBM bytes per launch / its mean duration
                       (HIP events around every kernel of extra, untimed, eagerly launched steps)
-                      (event_pair_floor_ms: what an event pair around a near-empty kernel reads in a busy stream)
+                      (event_pair_floor_ms: what an event pair around a near-empty kernel reads in a busy stream;
+                      frac_net_of_event_floor: the same launches with that floor taken off, beside the raw frac)
   roofline_decode_step / roofline_prefill   whole-phase figures from the timed region
   measured_copy_bandwidth   read + written bytes per second of a plain 1 GiB device copy on the same stream: the achievable
                       figure beside the published peak (roofline_decode_step.frac_of_measured_copy relates the step to it)
@@ -574,6 +575,11 @@ def main():
         # what an event pair around a near-empty kernel reads in the middle of a busy stream: the part of avg_launch_ms that
         # is dispatch and event handling rather than the kernel (a kernel trace's durations are shorter by about this much)
         roofline["event_pair_floor_ms"] = event_pair_floor(dev, stream)
+        # the same launches net of that floor (what a kernel trace's durations correspond to); `achieved` / `frac` stay raw
+        net_ms = kernels[dom]["avg_ms"] - roofline["event_pair_floor_ms"]
+        if net_ms > 0:
+            roofline["avg_launch_ms_net_of_event_floor"] = round(net_ms, 5)
+            roofline["frac_net_of_event_floor"] = round(per_bytes[dom] / (net_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
     cpu = None
     if not args.no_cpu_baseline and shape.weight_dtype < 2:   # (the weight-only quantised workloads are not the bench line)
