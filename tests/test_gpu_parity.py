@@ -298,6 +298,15 @@ def test_largest_batch_the_configuration_allows():
     check(run_job(MID64, lens, 2, seed=94), "batch 1024", strict=True)
 
 
+@pytest.mark.parametrize("shape", [WIDE1B, WIDE1B_QKN])
+def test_batches_so_large_that_no_decode_gemm_splits_k(shape):
+    """576 sequences on the 1B-wide layers: nine groups of 64 tokens times the row tiles of every matrix exceed the
+    number of compute units, so the QKV, O and down GEMMs run without split-K and finish in their own epilogues (no
+    hand-over), and the gate/up GEMM runs its eight-wavefront form once per token group"""
+    lens = 1 + synth.uniform_i32(53, 11, 576, 6)
+    check(run_job(shape, lens, 2, seed=95, gain_std=0.05), f"{shape.name} batch 576", strict=True)
+
+
 # ------------------------------------------------------------------ fp8 weight-only models
 MID128_FP8 = dataclasses.replace(MID128, name="mid128fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=24)
 MID64_FP8 = dataclasses.replace(MID64, name="mid64fp8", weight_dtype=synth.WDTYPE_FP8WO, seed=25)
