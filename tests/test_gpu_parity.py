@@ -117,6 +117,14 @@ def test_batch_sizes_cross_token_group_boundaries(batch):
     check(run_job(MID64, lens, 3, seed=40 + batch), f"batch {batch}")
 
 
+@pytest.mark.parametrize("batch", [20, 40])
+def test_fp32_weights_at_two_and_four_token_groups(batch):
+    """weights given in fp32 are carried as hi + lo planes (three MFMA passes); here with 2 and with 4 token groups per
+    workgroup, the instantiations with the most live registers"""
+    lens = 2 + synth.uniform_i32(batch, 9, batch, 30)
+    check(run_job(MIDF32, lens, 3, seed=60 + batch), f"fp32 weights, batch {batch}")
+
+
 def test_chunked_prefill_matches_oracle():
     check(run_job(MID128, [200, 75, 33], 3, seed=50, chunk=48), "chunked prefill (48)")
 
