@@ -1,6 +1,7 @@
 // Continuous-batching scheduler of a provider's serving loop (host only): admission queue, KV-block allocator with a
 // free list, chunked prefill under a per-iteration token budget, and the load figures a Model Manager polls (App. B
 // of the paper: active and queued requests, memory utilisation; App. C: target utilisation).
+#include <stddef.h>
 #include <stdint.h>
 
 #include <deque>
@@ -55,6 +56,10 @@ WWW_EXPORT int www_sched_create(const www_sched_config* cfg, www_sched** out) {
       cfg->kv_block_size != 16 || cfg->reserved != 0 || cfg->num_kv_blocks == 0 || cfg->num_kv_blocks > 0x7fffffffull ||
       !(cfg->target_utilisation > 0.0 && cfg->target_utilisation <= 1.0)) {
     set_error("scheduler configuration: counts must be positive, kv_block_size 16, 0 < target_utilisation <= 1");
+    return WWW_E_BAD_CONFIG;
+  }
+  if (cfg->chunk_tokens > cfg->token_budget) {  // a full chunk would never fit an iteration: its sequence could not progress
+    set_error("scheduler configuration: chunk_tokens %u exceeds token_budget %u", cfg->chunk_tokens, cfg->token_budget);
     return WWW_E_BAD_CONFIG;
   }
   www_sched* s = new (std::nothrow) www_sched;

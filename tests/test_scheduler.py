@@ -150,5 +150,27 @@ def test_library_rejects_what_it_cannot_serve():
         g.commit()
         with pytest.raises(B.WwwError):
             B.Scheduler(2, 4, 32, 16, 10, target_utilisation=1.5)
+        with pytest.raises(B.WwwError) as e:               # a full chunk that can never fit an iteration's budget
+            B.Scheduler(2, 4, token_budget=16, chunk_tokens=32, num_kv_blocks=10)
+        assert e.value.code == B.E_BAD_CONFIG
+    finally:
+        g.close()
+
+
+def test_a_chunk_as_large_as_the_budget_still_makes_progress():
+    """chunk_tokens == token_budget is the tightest configuration that is accepted: one full chunk per iteration, every
+    request finishes"""
+    g = B.Scheduler(max_batch=3, max_blocks_per_seq=8, token_budget=32, chunk_tokens=32, num_kv_blocks=24, target_utilisation=1.0)
+    try:
+        for r, plen in enumerate((100, 32, 7)):
+            g.submit(r, plen, 3)
+        for it in range(200):
+            pre, dec = g.plan()
+            assert pre or dec, f"iteration {it}: nothing planned although requests are active"
+            assert sum(e[1] for e in pre) <= 32
+            g.commit()
+            if g.stats()["active"] == 0 and g.stats()["queued"] == 0:
+                break
+        assert g.stats()["finished"] == 3
     finally:
         g.close()
