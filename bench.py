@@ -9,8 +9,8 @@ a HIP graph, tokens fed back on the device).  Prints ONE JSON line:
   prefill_tokens_per_s prompt tokens per second of the prefill calls in the same steps
   roofline            dominant decode kernel: algorithmic HBM bytes per launch / its mean duration
                       (HIP events around every kernel of extra, untimed, eagerly launched steps)
-                      (event_pair_floor_ms: what an event pair around a near-empty kernel reads in a busy stream;
-                      frac_net_of_event_floor: the same launches with that floor taken off, beside the raw frac)
+                      (event_pair_floor_ms: what an event pair around a near-empty kernel reads in a busy stream, for
+                      information; whole_step_frac repeats roofline_decode_step.frac, the figure the target is about)
   roofline_decode_step / roofline_prefill   whole-phase figures from the timed region
   measured_copy_bandwidth   read + written bytes per second of a plain 1 GiB device copy on the same stream: the achievable
                       figure beside the published peak (roofline_decode_step.frac_of_measured_copy relates the step to it)
@@ -571,15 +571,13 @@ def main():
                     "algorithmic_bytes_per_launch": int(per_bytes[dom]), "avg_launch_ms": kernels[dom]["avg_ms"]}
 
     copy_peak = measured_copy_bandwidth(dev, stream)
+    mfma_rate = measured_mfma_rate(dev, stream)
     if roofline:
         # what an event pair around a near-empty kernel reads in the middle of a busy stream: the part of avg_launch_ms that
         # is dispatch and event handling rather than the kernel (a kernel trace's durations are shorter by about this much)
         roofline["event_pair_floor_ms"] = event_pair_floor(dev, stream)
-        # the same launches net of that floor (what a kernel trace's durations correspond to); `achieved` / `frac` stay raw
-        net_ms = kernels[dom]["avg_ms"] - roofline["event_pair_floor_ms"]
-        if net_ms > 0:
-            roofline["avg_launch_ms_net_of_event_floor"] = round(net_ms, 5)
-            roofline["frac_net_of_event_floor"] = round(per_bytes[dom] / (net_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        # the whole decode step beside its dominant kernel: the figure the 70 % target is about
+        roofline["whole_step_frac"] = round(step_gbs / HBM_PEAK_GBS, 4)
 
     cpu = None
     if not args.no_cpu_baseline and shape.weight_dtype < 2:   # (the weight-only quantised workloads are not the bench line)
@@ -600,7 +598,9 @@ def main():
                                  "frac_of_measured_copy": round(step_gbs / copy_peak["GBps"], 4)},
         "measured_copy_bandwidth": copy_peak,
         "roofline_prefill": {"bound": "mfma", "achieved": round(pre_tflops, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                             "frac": round(pre_tflops / MFMA_PEAK_TFLOPS, 4), "algorithmic_flops": pf},
+                             "frac": round(pre_tflops / MFMA_PEAK_TFLOPS, 4), "algorithmic_flops": pf,
+                             "frac_of_measured_mfma_loop": round(pre_tflops / mfma_rate["TFLOPs"], 4)},
+        "measured_mfma_loop": mfma_rate,
         "decode_kernels": kernels,
         "cpu_baseline": cpu,
         "wall_s_timed_region": round(wall, 3),
@@ -632,6 +632,30 @@ def measured_copy_bandwidth(dev, stream):
     torch.cuda.empty_cache()
     ms = float(np.median(times))
     return {"GBps": round(2 * nbytes / ms * 1e-6, 1), "what": "device-to-device copy of 1 GiB, read + written bytes, median of 5 after 2 warm-up"}
+
+
+def measured_mfma_rate(dev, stream):
+    """What a loop of nothing but fp16 MFMAs on register operands sustains on this GPU (www_debug_mfma_loop: two workgroups
+    of four wavefronts per compute unit, pseudo-random operands): the achievable figure beside the published dense peak
+    that the prefill fraction is quoted against."""
+    import torch
+    from paper_2603_20661_amd import binding as B
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    wgs, iters = 8 * cus, 12000
+    sink = torch.empty(wgs * 4, dtype=torch.float32, device=dev)
+    times, flops = [], 0.0
+    with torch.cuda.stream(stream):
+        for it in range(7):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            flops = B.www_debug_mfma_loop(wgs, iters, sink, stream=stream)
+            e1.record(stream)
+            stream.synchronize()
+            if it >= 2:
+                times.append(e0.elapsed_time(e1))
+    ms = float(np.median(times))
+    return {"TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1), "ms": round(ms, 3),
+            "what": f"{wgs} workgroups x 4 wavefronts x {iters} rounds of 8 independent 32x32x16 fp16 MFMAs on register operands, median of 5 after 2 warm-up"}
 
 
 def event_pair_floor(dev, stream):

@@ -22,10 +22,15 @@
  *    Calls on one model must not overlap: they share the model's workspace.
  *  - Return value: 0 on success, a negative WWW_E_* code otherwise; www_last_error() then gives
  *    a message for the calling thread.  Argument checks run on the host before anything is
- *    launched.  Contents of device arrays (token ids, block ids, lengths) are NOT checked: the
- *    caller guarantees  0 <= token < vocab,  0 <= block id < num_kv_blocks for every block a
- *    sequence uses, distinct blocks for distinct (sequence, position/16), and
- *    q_lens <= seq_lens <= max_blocks_per_seq * 16.
+ *    launched.  Contents of device arrays (token ids, block ids, lengths) are by default NOT
+ *    checked: the caller guarantees  0 <= token < vocab,  0 <= block id < num_kv_blocks for every
+ *    block a sequence uses, distinct blocks for distinct (sequence, position/16) of a call, and
+ *    1 <= q_lens <= seq_lens <= max_blocks_per_seq * 16.
+ *  - Validation mode: with the environment variable WWW_VALIDATE=1 set when www_model_load runs,
+ *    every www_prefill / www_decode_step of that model first checks exactly those conditions with a
+ *    small kernel, WAITS for it on the stream, and returns WWW_E_INVALID_ARG without launching
+ *    anything else if one is violated (the message names which).  The mode costs a stream
+ *    synchronisation per call and cannot be used on a stream the caller is capturing.
  *
  * Weight blob (source format, device memory, may be released after www_model_load returns).
  * Tensors in this order, each starting on a 256-byte boundary, every matrix row-major
@@ -145,6 +150,12 @@ void www_model_free(www_model* m);
 /* Message of the last error on this thread ("" if none); storage is thread-local and static. */
 const char* www_last_error(void);
 
+/* Waits for the work enqueued on hip_stream and reports what its kernels found: WWW_E_STALE if a split-K hand-over
+ * saw its placement rule violated since the last check (see WWW_E_STALE; the model switches to the fenced hand-over),
+ * else WWW_OK.  www_prefill / www_decode_step make the same check on entry, i.e. for the calls BEFORE them; a caller
+ * that wants the verdict on the last call's results before using them calls this.  Errors: INVALID_ARG, HIP, STALE. */
+int www_check(www_model* m, void* hip_stream);
+
 /* Test hook: physical token slot of (block-table row, position), computed on the device by the same
  * routine the cache-writing kernels use.  table_row_dev int32 [n_blocks]; positions_dev int32 [n];
  * slots_dev int64 [n] receives block * 16 + position % 16.  Errors: INVALID_ARG, HIP. */
@@ -152,8 +163,8 @@ int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, 
 
 /* Test hook: copies an internal fp32 buffer of the last call to host memory after synchronising the
  * stream.  which: 0 = residual stream of the decode path [batch][d_model]; 1 = the decode path's query buffer and
- * 2 = its packed attention output, both as raw 32-bit words.
- * Errors: INVALID_ARG, HIP. */
+ * 2 = its packed attention output, both as raw 32-bit words.  Ends with the check of www_check.
+ * Errors: INVALID_ARG, HIP, STALE. */
 int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floats, void* hip_stream);
 
 /* Benchmark hook: per-kernel timing of decode steps.  While enabled, www_decode_step launches its
@@ -165,6 +176,13 @@ int www_debug_read(www_model* m, int32_t which, float* dst_host, uint64_t n_floa
  * read, then clears them.  Errors: INVALID_ARG, HIP. */
 int www_debug_profile(www_model* m, int32_t enable);
 int www_debug_profile_read(www_model* m, float* ms_host, int32_t* launches_host, void* hip_stream);
+
+/* Benchmark hook: launches a kernel of `workgroups` workgroups of four wavefronts that does nothing but `iters` rounds of
+ * eight independent fp16 32x32x16 MFMAs per wavefront on pseudo-random register operands (no memory traffic), and
+ * writes one float per wavefront to sink_dev [workgroups * 4] so that the work cannot be dropped.  *flops_out (host,
+ * may be NULL) receives the floating-point operations of the launch; the caller times it.  This is the measured
+ * matrix-core rate of the GPU at hand, to set beside the published dense peak.  Errors: INVALID_ARG, HIP. */
+int www_debug_mfma_loop(int32_t workgroups, int32_t iters, float* sink_dev, double* flops_out, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Duel bookkeeping (Sec. 4.2 "Duel-and-Judge Mechanism"; Sec. 5, Assumptions 2 and 3).

@@ -21,7 +21,7 @@ EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step"
            "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
            "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
            "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
-           "www_get_stats", "www_sample_top_p")
+           "www_get_stats", "www_sample_top_p", "www_check", "www_debug_mfma_loop")
 FLAG_QK_NORM = 1
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
@@ -79,6 +79,10 @@ def _load_library():
     L.www_model_free.restype = None
     L.www_last_error.argtypes = []
     L.www_last_error.restype = ctypes.c_char_p
+    L.www_debug_mfma_loop.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.www_debug_mfma_loop.restype = ctypes.c_int
+    L.www_check.argtypes = [vp, vp]
+    L.www_check.restype = ctypes.c_int
     L.www_debug_slots.argtypes = [vp, vp, i32, vp, vp]
     L.www_debug_read.argtypes = [vp, i32, vp, ctypes.c_uint64, vp]
     L.www_debug_profile.argtypes = [vp, i32]
@@ -191,6 +195,19 @@ def www_decode_step(model: Model, last_tokens, seq_lens, block_table, logits=Non
         assert logits.shape == (batch, model.cfg.vocab)
     _check(lib.www_decode_step(model._h, _ptr(last_tokens, i32), _ptr(seq_lens, i32), _ptr(block_table, i32), batch,
                                _ptr(logits, torch.float32), _ptr(next_tokens, i32), _stream(stream)))
+
+
+def www_debug_mfma_loop(workgroups: int, iters: int, sink, stream=None) -> float:
+    """launches the pure-MFMA loop; sink fp32 [workgroups * 4]; -> floating-point operations of the launch"""
+    assert sink.numel() >= workgroups * 4
+    flops = ctypes.c_double()
+    _check(lib.www_debug_mfma_loop(workgroups, iters, _ptr(sink, torch.float32), ctypes.byref(flops), _stream(stream)))
+    return flops.value
+
+
+def www_check(model: Model, stream=None):
+    """waits for the stream; raises WwwError(E_STALE) if a kernel of the finished work reported a hand-over violation"""
+    _check(lib.www_check(model._h, _stream(stream)))
 
 
 def www_debug_slots(table_row, positions, stream=None):

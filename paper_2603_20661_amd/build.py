@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwww.so")
-SOURCES = ["api.hip", "pack.hip", "decode.hip", "prefill.hip", "duel.hip", "sample.hip", "sched.cpp", "ledger.cpp"]   # the .cpp files are host-only C++
+SOURCES = ["api.hip", "pack.hip", "decode.hip", "prefill.hip", "duel.hip", "sample.hip", "probe.hip", "sched.cpp", "ledger.cpp"]   # the .cpp files are host-only C++
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-fvisibility=hidden", "-fvisibility-inlines-hidden",

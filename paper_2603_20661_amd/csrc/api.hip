@@ -118,6 +118,7 @@ struct Plan {
   uint64_t zero_begin, zero_end;  // region cleared at load (counters, padded activation buffers)
   uint64_t h, ssq, q, xq, xo, xa, partial, attn_part, counters, logits, last_tok, argmax_val, argmax_idx, attn_hdr, attn_start, attn_pref;
   uint64_t hp, ssq_p, xn, qp, op, ap, row_seq, row_pos, tile_seq, tile_q0, meta;
+  uint64_t val_words, val_bitmap, val_bitmap_bytes;  // argument validation (WWW_VALIDATE=1): result words, one bit per KV block
   int attn_maxrec;
 };
 
@@ -227,6 +228,9 @@ static void make_plan(const www_config* c, Plan& p) {
   p.tile_seq = take(max_tiles * 4);
   p.tile_q0 = take(max_tiles * 4);
   p.meta = take((16 + 2 * ((uint64_t)s.maxB + 1)) * 4);
+  p.val_words = take(256);
+  p.val_bitmap_bytes = ((uint64_t)c->num_kv_blocks + 31) / 32 * 4;
+  p.val_bitmap = take(p.val_bitmap_bytes);
   p.zero_end = off;
   p.total = off;
 }
@@ -247,6 +251,69 @@ static uint64_t blob_bytes(const www_config* c) {
            (s.qk_norm ? 2 * align256((uint64_t)s.hd * 4) : 0);
   off += align256((uint64_t)s.d * 4) + blob_matrix_bytes(s, s.V, s.d);
   return off;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Opt-in validation of the device-resident arguments of a call (environment variable WWW_VALIDATE=1, read when a model
+// is loaded).  One small kernel checks every token id, every length and every block id the call would use and marks
+// each block in a bitmap (a block named twice is an error); the host waits for it and launches nothing else if
+// anything is out of range.
+enum { VAL_TOKEN = 1, VAL_LENGTH = 2, VAL_BLOCK = 4, VAL_DUPLICATE = 8, VAL_TOTAL = 16 };
+
+__global__ __launch_bounds__(256) void validate_args_kernel(const int32_t* __restrict__ tokens, int n_tokens, const int32_t* __restrict__ q_lens,
+                                                            const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ table,
+                                                            int batch, int mbs, int vocab, int64_t num_blocks,
+                                                            unsigned* __restrict__ bitmap, int* __restrict__ out) {
+  const int stride = gridDim.x * 256, first = blockIdx.x * 256 + threadIdx.x;
+  unsigned bad = 0;
+  long long qsum = 0;
+  for (int i = first; i < n_tokens; i += stride)
+    if (tokens[i] < 0 || tokens[i] >= vocab) bad |= VAL_TOKEN;
+  for (int b = first; b < batch; b += stride) {
+    const int q = q_lens ? q_lens[b] : 1, n = seq_lens[b];
+    if (q < 1 || n < q || n > mbs * KV_BS) bad |= VAL_LENGTH;
+    qsum += q;
+  }
+  // block-table entries in use: entry j of row b for j < ceil(seq_lens[b] / 16) (rows with a bad length are skipped)
+  for (long long e = first; e < (long long)batch * mbs; e += stride) {
+    const int b = (int)(e / mbs), j = (int)(e % mbs), n = seq_lens[b];
+    if (n < 1 || n > mbs * KV_BS || j >= (n + KV_BS - 1) / KV_BS) continue;
+    const int id = table[e];
+    if (id < 0 || id >= num_blocks) { bad |= VAL_BLOCK; continue; }
+    const unsigned bit = 1u << (id & 31);
+    if (atomicOr(&bitmap[id >> 5], bit) & bit) bad |= VAL_DUPLICATE;
+  }
+  if (bad) atomicOr((unsigned*)&out[0], bad);
+  if (qsum) atomicAdd(&out[1], (int)qsum);
+}
+
+// Runs the check on `st` and waits for it.  WWW_OK, or WWW_E_INVALID_ARG with a message naming what was found.
+static int validate_device_args(www_model* m, const int32_t* tokens, int n_tokens, const int32_t* q_lens, const int32_t* seq_lens,
+                                const int32_t* table, int batch, hipStream_t st) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone) {
+    set_error("WWW_VALIDATE=1 waits for the stream and cannot run on a stream that is being captured");
+    return WWW_E_INVALID_ARG;
+  }
+  HIP_TRY(hipMemsetAsync(m->val_words, 0, 256, st));
+  HIP_TRY(hipMemsetAsync(m->val_bitmap, 0, m->val_bitmap_bytes, st));
+  const long long work = (long long)batch * m->cfg.max_blocks_per_seq > n_tokens ? (long long)batch * m->cfg.max_blocks_per_seq : n_tokens;
+  int grid = (int)((work + 255) / 256);
+  if (grid < 1) grid = 1;
+  if (grid > 1024) grid = 1024;
+  hipLaunchKernelGGL(validate_args_kernel, dim3(grid), dim3(256), 0, st, tokens, n_tokens, q_lens, seq_lens, table, batch,
+                     (int)m->cfg.max_blocks_per_seq, m->V, (int64_t)m->cfg.num_kv_blocks, m->val_bitmap, m->val_words);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(m->fault_host + 1, m->val_words, 8, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  const int flags = m->fault_host[1], qsum = m->fault_host[2];
+  int bad = flags | (!(flags & VAL_LENGTH) && qsum != n_tokens ? VAL_TOTAL : 0);
+  if (!bad) return WWW_OK;
+  set_error("device arguments rejected (WWW_VALIDATE=1):%s%s%s%s%s; nothing was launched",
+            bad & VAL_TOKEN ? " token id outside [0, vocab)" : "", bad & VAL_LENGTH ? " lengths violate 1 <= q_len <= seq_len <= 16 * max_blocks_per_seq" : "",
+            bad & VAL_BLOCK ? " block id outside [0, num_kv_blocks)" : "", bad & VAL_DUPLICATE ? " a block id is used twice in the call" : "",
+            bad & VAL_TOTAL ? " the lengths of the new tokens do not add up to total_q_tokens" : "");
+  return WWW_E_INVALID_ARG;
 }
 
 WWW_EXPORT int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_bytes, uint64_t* kv_pool_bytes, uint64_t* workspace_bytes) {
@@ -407,13 +474,20 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
     if (ok < 0) { set_error("placement probe failed: %s", hipGetErrorString(hipGetLastError())); return fail(WWW_E_HIP); }
     m->handover_fence = (ok == 0) || (force && atoi(force) != 0);
     // a pinned host word the kernels set if, against the probe, the splits of a row tile ever run on different XCDs
-    if (hipHostMalloc((void**)&m->fault_host, sizeof(int), hipHostMallocMapped) != hipSuccess ||
+    if (hipHostMalloc((void**)&m->fault_host, 4 * sizeof(int), hipHostMallocMapped) != hipSuccess ||
         hipHostGetDevicePointer((void**)&m->fault_dev, m->fault_host, 0) != hipSuccess) {
       set_error("pinned flag allocation failed: %s", hipGetErrorString(hipGetLastError()));
       if (m->fault_host) (void)hipHostFree(m->fault_host);
       return fail(WWW_E_HIP);
     }
     *m->fault_host = 0;
+  }
+  {
+    const char* v = getenv("WWW_VALIDATE");
+    m->validate = v && atoi(v) != 0;
+    m->val_words = (int*)(ws + p.val_words);
+    m->val_bitmap = (unsigned*)(ws + p.val_bitmap);
+    m->val_bitmap_bytes = p.val_bitmap_bytes;
   }
   *out = m;
   return WWW_OK;
@@ -430,6 +504,8 @@ WWW_EXPORT int www_prefill(www_model* m, const int32_t* tokens_dev, const int32_
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
   if (total_q_tokens > m->maxT) { set_error("total_q_tokens %d exceeds max_prefill_tokens %d", total_q_tokens, m->maxT); return WWW_E_CAPACITY; }
   hipStream_t st = (hipStream_t)hip_stream;
+  if (m->validate)
+    if (int rcv = validate_device_args(m, tokens_dev, total_q_tokens, q_lens_dev, seq_lens_dev, block_table_dev, batch, st)) return rcv;
   int rc = run_prefill(m, tokens_dev, q_lens_dev, seq_lens_dev, block_table_dev, batch, total_q_tokens, st);
   if (rc) return rc;
   // the last new position of every sequence goes through the decode path (hi/lo activations), which also yields the logits
@@ -445,6 +521,8 @@ WWW_EXPORT int www_decode_step(www_model* m, const int32_t* last_tokens_dev, con
   if (!last_tokens_dev || !seq_lens_dev || !block_table_dev) { set_error("NULL pointer argument"); return WWW_E_INVALID_ARG; }
   if (batch > m->maxB) { set_error("batch %d exceeds max_batch %d", batch, m->maxB); return WWW_E_CAPACITY; }
   hipStream_t st = (hipStream_t)hip_stream;
+  if (m->validate)
+    if (int rcv = validate_device_args(m, last_tokens_dev, batch, nullptr, seq_lens_dev, block_table_dev, batch, st)) return rcv;
   if (!m->use_graph || st == nullptr || (m->prof && m->prof->on))  // the legacy default stream cannot be captured
     return run_decode(m, last_tokens_dev, seq_lens_dev, block_table_dev, batch, logits_dev, next_tokens_dev, st);
 
@@ -494,6 +572,12 @@ WWW_EXPORT void www_model_free(www_model* m) {
 
 WWW_EXPORT const char* www_last_error(void) { return g_err; }
 
+WWW_EXPORT int www_check(www_model* m, void* hip_stream) {
+  if (!m) { set_error("NULL model"); return WWW_E_INVALID_ARG; }
+  HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+  return check_placement_fault(m);
+}
+
 WWW_EXPORT int www_debug_slots(const int32_t* table_row_dev, const int32_t* positions_dev, int32_t n, int64_t* slots_dev, void* hip_stream) {
   if (!table_row_dev || !positions_dev || !slots_dev || n < 0) { set_error("bad argument"); return WWW_E_INVALID_ARG; }
   if (launch_debug_slots(table_row_dev, positions_dev, n, slots_dev, (hipStream_t)hip_stream)) { set_error("launch failed"); return WWW_E_HIP; }
@@ -511,7 +595,7 @@ WWW_EXPORT int www_debug_read(www_model* m, int32_t which, float* dst_host, uint
   if (n_floats > cap) { set_error("buffer holds %llu floats", (unsigned long long)cap); return WWW_E_INVALID_ARG; }
   HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
   HIP_TRY(hipMemcpy(dst_host, src, n_floats * 4, hipMemcpyDeviceToHost));
-  return WWW_OK;
+  return check_placement_fault(m);  // the work is complete: a violation found by its kernels is reported now, not by the next call
 }
 
 WWW_EXPORT int www_debug_profile(www_model* m, int32_t enable) {

@@ -129,8 +129,12 @@ struct www_model {
   float* argmax_val;  // [maxB][32] per-slice maxima of the logits and
   int* argmax_idx;    // their indices
   unsigned long long* counters;  // split-K arrival counters
-  int* fault_host;  // pinned host word the kernels set when the placement rule of the split-K hand-over is violated,
-  int* fault_dev;   // and its device address
+  int* fault_host;  // pinned host words: [0] set by the kernels when the placement rule of the split-K hand-over is violated,
+  int* fault_dev;   // (its device address); [1], [2] receive the result words of the argument validation
+  int validate;     // 1: every call first checks its device-resident arguments (WWW_VALIDATE=1 at load)
+  int* val_words;   // device: [0] flags of what the check found, [1] sum of the new-token counts
+  unsigned* val_bitmap;  // device: one bit per KV block, to find a block that is named twice
+  uint64_t val_bitmap_bytes;
   float* logits_buf;  // used when the caller passes no logits buffer
   int* last_tok;      // [maxB] tokens of the last prompt position (prefill)
   // prefill-path buffers

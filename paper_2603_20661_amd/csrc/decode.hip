@@ -484,6 +484,9 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
     }
     __syncthreads();
     if (!*s_last) return;
+    // the fenced hand-over's other half: the partial tiles may come from another L2, so everything this workgroup has
+    // cached is dropped before they are read (acquire side of the producers' release fences)
+    if (p.fence_handover) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (tid == 0) __hip_atomic_store(&p.counters[zb * p.row_tiles + tile], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     request_epilogue_inputs();
 #pragma unroll
@@ -702,7 +705,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
         const int mid = (lo + hi + 1) >> 1;
         if ((int64_t)pref[mid] * Hkv <= x0) lo = mid; else hi = mid - 1;
       }
-      const int P = pref[lo + 1] - pref[lo];
+      const int P = max(1, pref[lo + 1] - pref[lo]);  // (never 0 for the sequence that holds entry x0 < T)
       const int r = (int)(x0 - (int64_t)pref[lo] * Hkv);
       sb = lo; sj = r / P; sp = r % P;
     }
@@ -817,13 +820,15 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        union { uint16_t s[8]; f16x8 v; } pb;
+        // the probabilities go to the matrix cores as fp16 hi + lo, like every other operand of the single-token path
+        // (the kernel waits for memory, the second pass over the values costs nothing): one rounding site less per layer
+        union { uint16_t s[8]; f16x8 v; } pb, pl;
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           float pv = __builtin_amdgcn_exp2f(sc[i] - m_new);
           psum += pv;
-          pb.s[i] = f32_to_f16_sat(pv);
+          split_f16(pv, pb.s[i], pl.s[i]);
         }
         l_run = l_run * alpha + psum;
         m_run = m_new;
@@ -839,6 +844,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
           const u32x4 a = {r.v0[f].x & a01, r.v0[f].y & a23, r.v1[f].x & b01, r.v1[f].y & b23};
           oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
           oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
+          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pl.v, oacc[f], 0, 0, 0);
         }
       };
 
@@ -1014,7 +1020,8 @@ __global__ __launch_bounds__(64) void argmax_final_kernel(const float* __restric
   int bi = lane < ARGMAX_CHUNKS ? pidx[blockIdx.x * ARGMAX_CHUNKS + lane] : 0x7fffffff;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) argmax_take(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
-  if (lane == 0) out[blockIdx.x] = bi;
+  // a row without any ordered value (all NaN) has no largest element: token 0, never an index outside the vocabulary
+  if (lane == 0) out[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
 }
 
 // ------------------------------------------------------------------------------------------------

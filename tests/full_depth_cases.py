@@ -103,3 +103,22 @@ class Stored:
         hit = gpu_logits.argmax(-1) == self.tokens
         gap = self.top_val[:, 0] - self.top_val[:, 1]
         return float(per_row.max()), per_row, int(hit.sum()), int((hit | (gap < 2 * per_row)).sum())
+
+
+class LiveRows:
+    """The same interface over oracle rows computed on the spot (every column of every row is compared)."""
+
+    def __init__(self, logits: np.ndarray):
+        self.logits = logits
+        order = np.argsort(-logits, axis=-1, kind="stable")[:, :2]
+        self.tokens = order[:, 0].astype(np.int32)
+        self.gap = np.take_along_axis(logits, order[:, :1], -1)[:, 0] - np.take_along_axis(logits, order[:, 1:2], -1)[:, 0]
+        self.rows = len(self.tokens)
+        self.full = logits
+
+    def compare(self, gpu_logits: np.ndarray):
+        assert gpu_logits.shape == self.logits.shape
+        assert np.isfinite(gpu_logits).all(), "non-finite logits from the GPU path"
+        per_row = np.abs(gpu_logits - self.logits).max(-1)
+        hit = gpu_logits.argmax(-1) == self.tokens
+        return float(per_row.max()), per_row, int(hit.sum()), int((hit | (self.gap < 2 * per_row)).sum())

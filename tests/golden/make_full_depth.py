@@ -19,7 +19,7 @@ sys.path.insert(0, os.path.dirname(HERE))                    # tests/
 sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))   # repository root
 
 import full_depth_cases as C                 # noqa: E402
-from oracle import oracle as O               # noqa: E402
+from helpers import oracle_greedy            # noqa: E402  (prefill + greedy steps through the oracle, nothing else)
 from paper_2603_20661_amd import synth       # noqa: E402
 
 
@@ -28,34 +28,7 @@ def log(msg):
 
 
 def greedy(shape, blob, prompts, steps, chunk=None):
-    """Each prompt alone through the oracle's prefill (optionally in chunks), then `steps` greedy decode steps of all of
-    them together.  Returns logits [len(prompts)][steps + 1, V]."""
-    n = len(prompts)
-    ctx = max(len(p) for p in prompts) + steps + 1
-    m = O.OracleModel(shape, blob, max_seqs=n, max_ctx=ctx)
-    rows = [[] for _ in range(n)]
-    last = np.zeros(n, np.int32)
-    for i, p in enumerate(prompts):
-        t0 = time.time()
-        step = len(p) if chunk is None else chunk
-        for a in range(0, len(p), step):
-            q = min(step, len(p) - a)
-            lg, nx, _ = m.forward(p[a:a + q], [q], [a + q], seq_ids=[i])
-        rows[i].append(lg[0])
-        last[i] = nx[0]
-        log(f"prefill of sequence {i} ({len(p)} tokens): {time.time() - t0:.0f} s")
-    cur = np.array([len(p) for p in prompts], np.int32)
-    t0 = time.time()
-    for s in range(steps):
-        cur = cur + 1
-        lg, nx, _ = m.forward(last, np.ones(n, np.int32), cur, seq_ids=np.arange(n, dtype=np.int32))
-        for i in range(n):
-            rows[i].append(lg[i])
-        last = nx.astype(np.int32)
-        if s % 32 == 31:
-            log(f"decode step {s + 1} of {steps}: {time.time() - t0:.0f} s")
-    m.close()
-    return [np.stack(r) for r in rows]
+    return oracle_greedy(shape, blob, prompts, steps, chunk=chunk, log=log)
 
 
 def main():

@@ -85,6 +85,42 @@ def oracle_replay(shape, blob, prompt, generated):
     return np.stack(out)
 
 
+def oracle_greedy(shape, blob, prompts, steps, chunk=None, log=None):
+    """The oracle on its own: each prompt alone through its prefill (optionally in chunks of `chunk` tokens), then `steps`
+    greedy decode steps of all sequences together, each fed its own previous token.  Returns one array per prompt,
+    logits [steps + 1, V]: row 0 after the prompt, row s after s generated tokens; the greedy tokens are their argmax
+    (lowest index on ties, as the oracle's own argmax)."""
+    import time
+    from oracle import oracle as O
+    n = len(prompts)
+    shape, blob = oracle_view(shape, blob)
+    m = O.OracleModel(shape, blob, max_seqs=n, max_ctx=max(len(p) for p in prompts) + steps + 1)
+    rows = [[] for _ in range(n)]
+    last = np.zeros(n, np.int32)
+    for i, p in enumerate(prompts):
+        t0 = time.time()
+        width = len(p) if chunk is None else chunk
+        for a in range(0, len(p), width):
+            q = min(width, len(p) - a)
+            lg, nx, _ = m.forward(p[a:a + q], [q], [a + q], seq_ids=[i])
+        rows[i].append(lg[0])
+        last[i] = nx[0]
+        if log:
+            log(f"prefill of sequence {i} ({len(p)} tokens): {time.time() - t0:.0f} s")
+    cur = np.array([len(p) for p in prompts], np.int32)
+    t0 = time.time()
+    for s in range(steps):
+        cur = cur + 1
+        lg, nx, _ = m.forward(last, np.ones(n, np.int32), cur, seq_ids=np.arange(n, dtype=np.int32))
+        for i in range(n):
+            rows[i].append(lg[i])
+        last = nx.astype(np.int32)
+        if log and s % 32 == 31:
+            log(f"decode step {s + 1} of {steps}: {time.time() - t0:.0f} s")
+    m.close()
+    return [np.stack(r) for r in rows]
+
+
 def oracle_job(shape, blob, lens, toks, steps, table, num_blocks, chunk=None):
     """Oracle: prefill (optionally in chunks) then `steps` greedy decode steps.
     Returns logits [steps+1, B, V] and the greedy tokens [steps+1, B]."""

@@ -21,9 +21,17 @@ MID64 = synth.ModelShape("mid64", 2, 256, 8, 4, 64, 704, 1024, 1e-5, 1e4, synth.
 MIDF32 = dataclasses.replace(MID64, name="midf32", weight_dtype=synth.WDTYPE_F32, seed=23)
 
 
-def run_job(shape, lens, steps, seed, chunk=None, permute=True, gain_std=0.1, std=0.02, num_blocks=None, blob=None, max_batch=None):
+MIN_ROWS = 256   # logit rows per case: enough for the 99 % agreement bar to be a statement about a rate
+WIDE_ROWS = 1024  # ... and for the full-width cases, whose logit errors (3e-3 .. 7e-3 over vocabularies of 32 000 and more) flip
+                  # an exact near-tie of the oracle's two best logits in 0.2 - 0.3 % of the rows
+
+
+def run_job(shape, lens, steps, seed, chunk=None, permute=True, gain_std=0.1, std=0.02, num_blocks=None, blob=None, max_batch=None,
+            min_rows=MIN_ROWS):
+    """`steps` is the least number of decode steps; more are taken until the case has `min_rows` logit rows."""
     lens = np.asarray(lens, np.int32)
     Bn = len(lens)
+    steps = max(steps, -(-min_rows // Bn) - 1)
     cap = lens + steps + 1
     mbs = int((cap.max() + 15) // 16)
     need = int(((cap + 15) // 16).sum())
@@ -40,20 +48,15 @@ def run_job(shape, lens, steps, seed, chunk=None, permute=True, gain_std=0.1, st
     return o_logits, o_tok, g_logits, g_tok
 
 
-def check(res, what, strict=False):
-    """max |dlogit| <= 3e-2 always.  Greedy agreement >= 99 % (strict, teacher-forced).  The auxiliary cases below have
-    only tens of samples over vocabularies of 1-2 k random logits, where an exact near-tie (oracle top-2 gap below twice
-    the measured logit error) turns up about once per few hundred samples; for them a single such near-tie flip is
-    accepted.  The named configurations (tiny, full-width 1B / 8B, the 8B bench configuration) are held to the strict bar."""
+def check(res, what):
+    """max |dlogit| <= 3e-2 and teacher-forced greedy agreement >= 99 %, both strict, on every case (each has at least
+    MIN_ROWS logit rows); the tie-aware figure is printed for information only."""
     err, agree, tie = compare(*res)
     n = res[1].size
     print(f"{what}: max|dlogit|={err:.3e} agreement={agree:.4f} tie-aware={tie:.4f} samples={n}", flush=True)
+    assert n >= MIN_ROWS, f"{what}: only {n} logit rows"
     assert err <= TOL, f"{what}: max |dlogit| {err}"
-    if strict or n >= 100:
-        assert agree >= AGREE, f"{what}: greedy agreement {agree}"
-    else:
-        mismatches = int(round((1 - agree) * n))
-        assert mismatches <= 1 and tie == 1.0, f"{what}: {mismatches} greedy mismatches, tie-aware agreement {tie}"
+    assert agree >= AGREE, f"{what}: greedy agreement {agree}"
 
 
 def test_slot_indexing_bit_exact():
@@ -99,7 +102,7 @@ def test_decode_path_alone_token_by_token():
 def test_tiny_config_prefill_and_decode():
     wl = synth.workload("tiny")
     res = run_job(wl.shape, wl.prompt_lens, wl.decode_steps, seed=0, gain_std=0.0)
-    check(res, "tiny", strict=True)
+    check(res, "tiny")
 
 
 @pytest.mark.parametrize("shape,lens,steps", [
@@ -166,7 +169,7 @@ def test_full_width_layers_at_bench_batch(shape, batch):
     device)."""
     lens = 1 + synth.uniform_i32(batch, 11, batch, 40)
     lens[0], lens[1] = 1, 16
-    check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+    check(run_job(shape, lens, 3, seed=80 + batch, gain_std=0.05, min_rows=WIDE_ROWS), f"{shape.name} B={batch}")
 
 
 # ------------------------------------------------------------------ models with normalised query / key heads
@@ -205,7 +208,7 @@ def test_normalised_heads_full_width_layers(shape, batch):
     wavefronts of the workgroup that finishes a split row tile)"""
     lens = 1 + synth.uniform_i32(batch, 11, batch, 40)
     lens[0], lens[1] = 1, 16
-    check(run_job(shape, lens, 3, seed=92, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+    check(run_job(shape, lens, 3, seed=92, gain_std=0.05, min_rows=WIDE_ROWS), f"{shape.name} B={batch}")
 
 
 _DIGEST_JOB = r"""
@@ -297,13 +300,13 @@ def test_widest_model_the_configuration_allows():
     shape = synth.ModelShape("max8192", 2, 8192, 64, 8, 128, 2048, 1024, 1e-5, 5e5, synth.WDTYPE_BF16, seed=51)
     lens = 1 + synth.uniform_i32(51, 11, 40, 30)
     lens[0], lens[1] = 300, 1
-    check(run_job(shape, lens, 2, seed=93, gain_std=0.05), "d_model 8192", strict=True)
+    check(run_job(shape, lens, 2, seed=93, gain_std=0.05, min_rows=WIDE_ROWS), "d_model 8192")
 
 
 def test_largest_batch_the_configuration_allows():
     """1024 sequences in one prefill call and in every decode step (16 groups of 64 tokens per decode GEMM)"""
     lens = 1 + synth.uniform_i32(52, 11, 1024, 20)
-    check(run_job(MID64, lens, 2, seed=94), "batch 1024", strict=True)
+    check(run_job(MID64, lens, 2, seed=94, min_rows=WIDE_ROWS), "batch 1024")
 
 
 @pytest.mark.parametrize("shape", [WIDE1B, WIDE1B_QKN])
@@ -312,7 +315,7 @@ def test_batches_so_large_that_no_decode_gemm_splits_k(shape):
     number of compute units, so the QKV, O and down GEMMs run without split-K and finish in their own epilogues (no
     hand-over), and the gate/up GEMM runs its eight-wavefront form once per token group"""
     lens = 1 + synth.uniform_i32(53, 11, 576, 6)
-    check(run_job(shape, lens, 2, seed=95, gain_std=0.05), f"{shape.name} batch 576", strict=True)
+    check(run_job(shape, lens, 2, seed=95, gain_std=0.05, min_rows=WIDE_ROWS), f"{shape.name} batch 576")
 
 
 # ------------------------------------------------------------------ fp8 weight-only models
@@ -355,14 +358,14 @@ def test_int4_weight_only_models(shape, lens, steps, chunk):
 def test_int4_weight_only_full_width_layers(shape, batch):
     lens = 1 + synth.uniform_i32(batch, 14, batch, 40)
     lens[0], lens[1] = 1, 16
-    check(run_job(shape, lens, 3, seed=180 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+    check(run_job(shape, lens, 3, seed=180 + batch, gain_std=0.05, min_rows=WIDE_ROWS), f"{shape.name} B={batch}")
 
 
 @pytest.mark.parametrize("shape,batch", [(WIDE8B_FP8, 64), (WIDE1B_FP8, 32), (WIDE8B_FP8, 70), (WIDE1B_FP8, 64)])
 def test_fp8_weight_only_full_width_layers(shape, batch):
     lens = 1 + synth.uniform_i32(batch, 13, batch, 40)
     lens[0], lens[1] = 1, 16
-    check(run_job(shape, lens, 3, seed=140 + batch, gain_std=0.05), f"{shape.name} B={batch}", strict=True)
+    check(run_job(shape, lens, 3, seed=140 + batch, gain_std=0.05, min_rows=WIDE_ROWS), f"{shape.name} B={batch}")
 
 
 @pytest.mark.parametrize("fence,batch", [("0", 32), ("1", 32), ("0", 64)])
@@ -532,3 +535,43 @@ def test_bench_configuration_sampled_against_oracle(name):
     agree = float((got.argmax(-1) == ref.argmax(-1)).mean())
     print(f"{name} bench configuration, sequence {b0} (len {lens[b0]}): max|dlogit|={err:.3e} agreement={agree:.3f}", flush=True)
     assert err <= TOL and agree == 1.0
+
+
+def test_values_close_to_the_fp16_limit():
+    """Operands are IEEE fp16 and are clamped to +-65504 on conversion.  Here the value rows of every layer's QKV matrix are
+    scaled by 2^14 (exact in bf16 and in fp16), so that the cached values (standard deviation 7 400, the largest of the
+    117 000 about 30 000), the probabilities-times-values products and the attention output that feeds the O projection
+    come close to that limit (checked on the packed operand the attention kernel wrote: within a factor of eight), and
+    nothing is clamped: the result still matches the oracle, which has no such limit.  (RMSNorm makes the rest of the network indifferent to the scale of the residual stream.)"""
+    import torch
+    from paper_2603_20661_amd import binding as B
+    shape = MID128
+    blob = synth.make_blob(shape, gain_std=0.1).copy()
+    entries, _ = synth.blob_layout(shape)
+    qd, kd = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    for name, off, rows, cols, dt in entries:
+        if name.endswith(".wqkv"):
+            w = blob[off:off + rows * cols * 2].view(np.uint16).reshape(rows, cols)
+            v = w[qd + kd:]
+            v[(v & 0x7F80) != 0] += np.uint16(14 << 7)          # bf16: exponent + 14
+    lens = np.array([150, 40, 1, 257], np.int32)
+    res = run_job(shape, lens, 3, seed=72, blob=blob)
+    check(res, "values near the fp16 limit")
+    # the operand of the O projection as the attention kernels left it after one more decode step of a fresh session
+    cap = lens + 2
+    mbs = int((cap.max() + 15) // 16)
+    nb = int(((cap + 15) // 16).sum()) + 3
+    toks = synth.tokens(72, int(lens.sum()), shape.vocab)
+    table = synth.block_tables(72, cap, nb, mbs, permute=True)
+    sess = GpuSession(shape, blob, len(lens), mbs * 16, int(lens.sum()), nb)
+    try:
+        _, nx = sess.prefill(toks, lens, lens, table)
+        sess.decode(nx, lens + 1, table)
+        raw = B.www_debug_read(sess.model, 2, 16 * qd, stream=sess.stream).numpy()       # one token group: hi and lo planes
+        halves = raw.view(np.float16).astype(np.float32)
+        assert np.isfinite(halves).all()
+        top = float(np.abs(halves).max())
+        print(f"largest fp16 operand of the O projection: {top:.0f}", flush=True)
+        assert 65504 / 8 < top < 65504
+    finally:
+        sess.close()
