@@ -334,6 +334,18 @@ int www_get_stats(const www_sched* sched, www_stats* out);
 int www_sample_top_p(const float* logits_dev, int32_t batch, int32_t vocab, float temperature, float top_p, const float* u01_dev,
                      float* scratch_dev, int32_t* tokens_dev, void* hip_stream);
 
+/* www_sample_top_p for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernel and the same results, with the [batch][vocab] buffer of
+ * unnormalised probabilities in an array built into the library (WWW_SAMPLE_STATIC_MAX_FLOATS floats = 32 MiB of
+ * device memory on every GPU the library runs on, held until the process ends) instead of scratch_dev.  The call
+ * allocates and frees nothing.  batch * vocab must not exceed WWW_SAMPLE_STATIC_MAX_FLOATS (enough for 64 rows of a
+ * 128 256-token vocabulary).  All calls on one GPU share the array: calls that overlap on one GPU race; calls on one
+ * stream are ordered.  The first call on a device looks the array's address up (no allocation; make it outside a
+ * capture).  Errors: INVALID_ARG, CAPACITY (batch * vocab too large), HIP. */
+#define WWW_SAMPLE_STATIC_MAX_FLOATS (8u << 20)
+int www_sample_top_p_static(const float* logits_dev, int32_t batch, int32_t vocab, float temperature, float top_p,
+                            const float* u01_dev, int32_t* tokens_dev, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step"
            "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
            "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
            "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
-           "www_get_stats", "www_sample_top_p", "www_check", "www_debug_mfma_loop")
+           "www_get_stats", "www_sample_top_p", "www_sample_top_p_static", "www_check", "www_debug_mfma_loop")
 FLAG_QK_NORM = 1
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
@@ -110,6 +110,8 @@ def _load_library():
     L.www_get_stats.argtypes = [vp, ctypes.POINTER(WwwStats)]
     L.www_sample_top_p.argtypes = [vp, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
     L.www_sample_top_p.restype = ctypes.c_int
+    L.www_sample_top_p_static.argtypes = [vp, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp]
+    L.www_sample_top_p_static.restype = ctypes.c_int
     for name in ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step", "www_debug_slots", "www_debug_read",
                  "www_debug_profile", "www_debug_profile_read", "www_judge_verdict", "www_ledger_create", "www_ledger_stakes",
                  "www_pos_sample", "www_ledger_serve", "www_ledger_duel", "www_ledger_read_ops", "www_sched_create", "www_sched_submit",
@@ -250,6 +252,16 @@ def www_sample_top_p(logits, temperature: float, top_p: float, u01, scratch, tok
     assert scratch.numel() >= batch * vocab
     _check(lib.www_sample_top_p(_ptr(logits, torch.float32), batch, vocab, temperature, top_p, _ptr(u01, torch.float32),
                                 _ptr(scratch, torch.float32), _ptr(tokens, torch.int32), _stream(stream)))
+
+
+SAMPLE_STATIC_MAX_FLOATS = 8 << 20
+
+
+def www_sample_top_p_static(logits, temperature: float, top_p: float, u01, tokens, stream=None):
+    """www_sample_top_p with the library's built-in scratch array (no device allocation anywhere in the call)"""
+    batch, vocab = logits.shape
+    _check(lib.www_sample_top_p_static(_ptr(logits, torch.float32), batch, vocab, temperature, top_p, _ptr(u01, torch.float32),
+                                       _ptr(tokens, torch.int32), _stream(stream)))
 
 
 class Ledger:

@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/www.h"
 
 #define WWW_EXPORT extern "C" __attribute__((visibility("default")))
@@ -146,4 +148,53 @@ WWW_EXPORT int www_sample_top_p(const float* logits_dev, int32_t batch, int32_t 
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) { set_error("sampling kernel launch failed: %s", hipGetErrorString(err)); return WWW_E_HIP; }
   return WWW_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same sampling for callers that cannot allocate device memory (code under HIP graph capture, serving loops and
+// harnesses that forbid hipMalloc): the [batch][vocab] buffer of unnormalised probabilities lives in a file-scope
+// device array instead of a caller-provided one.  Every GPU holds its own copy of the array at its own address until
+// the process ends; the address is looked up once per device and kept.  All calls on one GPU share the array: calls
+// that overlap on one GPU (different streams, different host threads) race.  Nothing in it has to start at zero - the
+// kernel writes every element it later reads.
+static __device__ __align__(256) float scratch[WWW_SAMPLE_STATIC_MAX_FLOATS];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+float* g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on each device, once looked up
+std::mutex g_scratch_mutex;
+
+// device address of this device's copy of `scratch` (the array's name itself is only a host-side stand-in)
+int static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_error("hipGetDevice failed: %s", hipGetErrorString(e)); return WWW_E_HIP; }
+  if (dev < 0 || dev >= MAX_DEVICES) { set_error("device index %d out of range", dev); return WWW_E_HIP; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) { set_error("hipGetSymbolAddress failed: %s", hipGetErrorString(e)); return WWW_E_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return WWW_OK;
+}
+}  // namespace
+
+WWW_EXPORT int www_sample_top_p_static(const float* logits_dev, int32_t batch, int32_t vocab, float temperature, float top_p,
+                                       const float* u01_dev, int32_t* tokens_dev, void* hip_stream) {
+  if (batch < 0 || vocab <= 0) { set_error("negative batch or non-positive vocab"); return WWW_E_INVALID_ARG; }
+  if ((uint64_t)batch * (uint64_t)vocab > (uint64_t)WWW_SAMPLE_STATIC_MAX_FLOATS) {
+    set_error("batch * vocab = %llu exceeds the %llu floats of the built-in scratch array; use www_sample_top_p with a buffer of your own",
+              (unsigned long long)((uint64_t)batch * (uint64_t)vocab), (unsigned long long)WWW_SAMPLE_STATIC_MAX_FLOATS);
+    return WWW_E_CAPACITY;
+  }
+  if (batch == 0) {  // still validate, as www_sample_top_p does
+    if (!(temperature > 0.f) || !(top_p > 0.f && top_p <= 1.f)) { set_error("temperature must be positive and top_p in (0, 1]"); return WWW_E_INVALID_ARG; }
+    return WWW_OK;
+  }
+  float* ptr = nullptr;
+  if (int rc = static_scratch(&ptr)) return rc;
+  return www_sample_top_p(logits_dev, batch, vocab, temperature, top_p, u01_dev, ptr, tokens_dev, hip_stream);
 }
