@@ -104,7 +104,7 @@ def decode_bytes_per_class(shape, ctx_lens, batch):
     the real context once per kv head, outputs written once; activations are not counted)."""
     d, F, V, L = shape.d_model, shape.ffn_dim, shape.vocab, shape.n_layers
     QD, KD = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
-    kv_tok_layer = 2 * KD * 2
+    kv_tok_layer = 2 * shape.n_kv_heads * (shape.head_dim * 2 + 4)   # 16-bit codes plus one fp32 scale per (kv head, K|V)
     # bytes per streamed weight: 16-bit, FP8 codes, or 4-bit codes plus a bf16 scale per group of 128 / 32
     wb = {0: 2, 1: 2, 2: 1, 3: 0.5 + 2 / 128, 4: 0.5 + 2 / 32}[shape.weight_dtype]
     return {
@@ -348,7 +348,7 @@ def bench_mixed(args):
         probe = B.make_config(shape, n_seq, mbs, budget, 1)
         _, _, ws_bytes = B.www_query_sizes(probe)
         free_bytes, _ = torch.cuda.mem_get_info()
-        block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * shape.head_dim * 2
+        block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * (shape.head_dim * 2 + 4)
         nb = int(0.90 * (free_bytes - ws_bytes)) // block_bytes
         table = synth.block_tables(2, cap, nb, mbs, permute=True)
         cfg = B.make_config(shape, n_seq, mbs, budget, nb)

@@ -41,7 +41,8 @@
  *                wo[d][Hq*hd], ffn_norm[d], wgu[2F][d] (gate rows, then up rows), wd[d][F]
  *     final_norm[d], lm_head[vocab][d]
  *
- * KV pool (device, caller-owned, contents opaque to the caller): 2 bytes per element, num_kv_blocks blocks of
+ * KV pool (device, caller-owned, contents opaque to the caller): 16-bit codes plus one fp32 scale per (token, kv head)
+ * vector of keys / values, i.e. 2 * head_dim + 4 bytes per vector (size from www_query_sizes), num_kv_blocks blocks of
  * kv_block_size = 16 token slots.  Logical position p of sequence b lives in block
  * block_table[b][p / 16], slot p % 16.
  */

@@ -323,7 +323,8 @@ WWW_EXPORT int www_query_sizes(const www_config* cfg, uint64_t* weight_blob_byte
   Plan p;
   make_plan(cfg, p);
   if (weight_blob_bytes) *weight_blob_bytes = blob_bytes(cfg);
-  if (kv_pool_bytes) *kv_pool_bytes = (uint64_t)cfg->num_kv_blocks * s.L * 2 * s.Hkv * KV_BS * s.hd * 2;
+  // 16-bit codes of every key and value element, then one fp32 scale per (token, kv head, K|V)
+  if (kv_pool_bytes) *kv_pool_bytes = (uint64_t)cfg->num_kv_blocks * s.L * 2 * s.Hkv * KV_BS * (s.hd * 2 + 4);
   if (workspace_bytes) *workspace_bytes = p.total;
   return WWW_OK;
 }
@@ -454,6 +455,8 @@ WWW_EXPORT int www_model_load(const www_config* cfg, const void* weights_dev, vo
   m->rope = (const float2*)(ws + p.rope);
   m->kv = (uint16_t*)kv_pool_dev;
   m->kv_plane = (int64_t)cfg->num_kv_blocks * s.Hkv * KV_BS * s.hd;
+  m->kv_scales = (float*)(m->kv + (int64_t)2 * s.L * m->kv_plane);
+  m->kv_scale_plane = (int64_t)cfg->num_kv_blocks * s.Hkv * 32;
   m->h = (float*)(ws + p.h); m->ssq = (float*)(ws + p.ssq); m->q_hi = (uint16_t*)(ws + p.q); m->q_lo = m->q_hi + (size_t)s.MTmax * 16 * s.QD;
   m->xq = (uint16_t*)(ws + p.xq); m->xo = (uint16_t*)(ws + p.xo); m->xa = (uint16_t*)(ws + p.xa);
   m->partial = (float*)(ws + p.partial); m->attn_part = (float*)(ws + p.attn_part); m->counters = (unsigned long long*)(ws + p.counters);

@@ -103,7 +103,8 @@ struct GemmP {
   // QKV epilogue
   uint16_t *q_hi, *q_lo;
   float qscale;
-  uint16_t *kplane, *vplane;  // this layer's K and V planes of the pool
+  uint16_t *kplane, *vplane;  // this layer's K and V planes of the pool (16-bit codes)
+  float* kvscale;             // and its plane of scales
   const int32_t *seq_lens, *table;
   int mbs, hd, Hq, Hkv;
   const float2* rope;
@@ -551,6 +552,58 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
     }
   }
 
+  // QKV: finish the values in place (RMSNorm factor, head normalisation, rotation), then take, per token, the largest
+  // magnitude of every head's vector (lanes, two cross-lane exchanges, the head's wavefronts through LDS): the scale of
+  // the key / value codes.  (Query heads get one too and ignore it.)
+  float head_amax[MTK];
+  if constexpr (EPI == EPI_QKV) {
+    const int rot_rows = (p.Hq + p.Hkv) * p.hd;
+#pragma unroll
+    for (int tb = 0; tb < MTK; ++tb) {
+      float am = 0.f;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const int n0 = (rg0 + r) * 16 + rsub;
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = acc[r][tb][i] * scale_pre[tb];
+        if (n0 < rot_rows) {
+          if (p.qk_gain) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] *= head_rs[tb] * gv_pre[r][i];
+          }
+          // rows arrive with the rotary pair (i, i + hd/2) at neighbouring positions (2i, 2i+1)
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr) {
+            const float cs_x = cs_pre[r][tb][2 * pr], cs_y = cs_pre[r][tb][2 * pr + 1];
+            float a = v[2 * pr], b = v[2 * pr + 1];
+            v[2 * pr] = a * cs_x - b * cs_y;
+            v[2 * pr + 1] = b * cs_x + a * cs_y;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[r][tb][i] = v[i];
+          am = fmaxf(am, __builtin_fabsf(v[i]));  // (a NaN element is dropped by fmaxf; its code is 0)
+        }
+      }
+      am = fmaxf(am, __shfl_xor(am, 16));
+      am = fmaxf(am, __shfl_xor(am, 32));
+      head_amax[tb] = am;
+    }
+    if (p.qk_gain) __syncthreads();  // `red` may still be read by the head normalisation above
+#pragma unroll
+    for (int tb = 0; tb < MTK; ++tb)
+      if (lane < 16) red[wave][tb * 16 + lane] = head_amax[tb];
+    __syncthreads();
+#pragma unroll
+    for (int tb = 0; tb < MTK; ++tb) {
+      const int at = tb * 16 + tsub;
+      head_amax[tb] = p.hd == 128 ? fmaxf(fmaxf(red[0][at], red[1][at]), fmaxf(red[2][at], red[3][at]))
+                                  : fmaxf(red[wave & 2][at], red[(wave & 2) + 1][at]);
+    }
+  }
+
 #pragma unroll
   for (int tb = 0; tb < MTK; ++tb) {
     const int t = (tb0 + tb) * 16 + tsub;
@@ -577,7 +630,7 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
         const int n0 = (rg0 + r) * 16 + rsub;
         float v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = acc[r][tb][i] * scale;
+        for (int i = 0; i < 4; ++i) v[i] = acc[r][tb][i] * scale;  // (QKV: overwritten below, the values are already final)
 
         if constexpr (EPI == EPI_LOGITS) {
           *reinterpret_cast<float4*>(p.logits + (int64_t)t * p.V + n0) = make_float4(v[0], v[1], v[2], v[3]);
@@ -594,23 +647,10 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
           }
           *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 0)) = hi.v;
           *reinterpret_cast<u32x2*>(p.xnext + packed_x_offset(n0, t, p.MT, 1)) = lo.v;
-        } else {  // EPI_QKV
-          const int rot_rows = (p.Hq + p.Hkv) * p.hd;
+        } else {  // EPI_QKV: the values were finished (scaled, normalised, rotated) in place above
           const int head = n0 / p.hd, c0 = n0 % p.hd;
-          if (n0 < rot_rows) {
-            if (p.qk_gain) {
 #pragma unroll
-              for (int i = 0; i < 4; ++i) v[i] *= head_rs[tb] * gv_pre[r][i];
-            }
-            // rows arrive with the rotary pair (i, i + hd/2) at neighbouring positions (2i, 2i+1)
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {
-              const float cs_x = cs_pre[r][tb][2 * pr], cs_y = cs_pre[r][tb][2 * pr + 1];
-              float a = v[2 * pr], b = v[2 * pr + 1];
-              v[2 * pr] = a * cs_x - b * cs_y;
-              v[2 * pr + 1] = b * cs_x + a * cs_y;
-            }
-          }
+          for (int i = 0; i < 4; ++i) v[i] = acc[r][tb][i];
           if (head < p.Hq) {
             // queries leave as fp16 hi + lo, already multiplied by log2(e)/sqrt(hd), in the order the attention kernel loads them
             union { uint16_t s[4]; u32x2 v; } qh, ql;
@@ -619,21 +659,25 @@ __global__ __launch_bounds__(256 * KH, 2 / KH) void skinny_gemm_kernel(const Gem
             *reinterpret_cast<u32x2*>(p.q_hi + (int64_t)t * (p.Hq * p.hd) + n0) = qh.v;
             *reinterpret_cast<u32x2*>(p.q_lo + (int64_t)t * (p.Hq * p.hd) + n0) = ql.v;
           } else {
+            // keys and values go to the cache as 16-bit codes with the scale of their (token, head) vector
             const int64_t slot = kv_slot_in_block(blk_pre[tb], pos_pre[tb]);
             const int64_t blk = slot / KV_BS;
             const int tok = (int)(slot % KV_BS);
-            if (head < p.Hq + p.Hkv) {
-              const int j = head - p.Hq;
-              union { uint16_t s[4]; u32x2 v; } kb16;
+            const bool is_v = head >= p.Hq + p.Hkv;
+            const int j = head - p.Hq - (is_v ? p.Hkv : 0);
+            const float inv = kv_code_inv(head_amax[tb]);
+            union { uint16_t s[4]; u32x2 v; } code;
 #pragma unroll
-              for (int i = 0; i < 4; ++i) kb16.s[i] = f32_to_f16_sat(v[i]);
-              *reinterpret_cast<u32x2*>(p.kplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = kb16.v;
+            for (int i = 0; i < 4; ++i) code.s[i] = kv_code(v[i], inv);
+            if (!is_v) {
+              *reinterpret_cast<u32x2*>(p.kplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = code.v;
             } else {
-              const int j = head - p.Hq - p.Hkv;
               uint16_t* dst = p.vplane + (blk * p.Hkv + j) * (int64_t)(KV_BS * p.hd);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) dst[v_cache_offset(tok, c0 + i)] = f32_to_f16_sat(v[i]);
+              for (int i = 0; i < 4; ++i) dst[v_cache_offset(tok, c0 + i)] = code.s[i];
             }
+            if (c0 == 0 && rsub == 0)  // one lane per (token, head): first row of the head
+              p.kvscale[kv_scale_offset(blk, p.Hkv, j) + (is_v ? 16 : 0) + tok] = kv_code_scale(head_amax[tb]);
           }
         }
       }
@@ -713,6 +757,28 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
   }
 }
 
+// Two 16-bit codes (one 32-bit word, offset binary u = x + 32768) as two pairs of fp16 numbers a, b with x = 256 a + b,
+// a in [-128, 127], b in [0, 255] - both exact in fp16, so the matrix cores multiply the codes without losing a bit.
+// The high and low bytes of u are planted in the mantissa of the fp16 number 1024 (0x6400 | n = 1024 + n) and
+// 1024 + 128, resp. 1024, is subtracted, two values per instruction.
+__device__ __forceinline__ void split_codes(uint32_t u, uint32_t& hi, uint32_t& lo) {
+  const f16x2 off_hi = {(_Float16)1152.f, (_Float16)1152.f}, off_lo = {(_Float16)1024.f, (_Float16)1024.f};
+  const uint32_t ph = __builtin_amdgcn_perm(0x64646464u, u, 0x04030401u);  // bytes: u.b1, 0x64, u.b3, 0x64
+  const uint32_t pl = __builtin_amdgcn_perm(0x64646464u, u, 0x04020400u);  // bytes: u.b0, 0x64, u.b2, 0x64
+  hi = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, ph) - off_hi);
+  lo = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, pl) - off_lo);
+}
+__device__ __forceinline__ void split_codes4(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, f16x8& hi, f16x8& lo) {
+  uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+  split_codes(w0, h0, l0);
+  split_codes(w1, h1, l1);
+  split_codes(w2, h2, l2);
+  split_codes(w3, h3, l3);
+  hi = as_f16x8(u32x4{h0, h1, h2, h3});
+  lo = as_f16x8(u32x4{l0, l1, l2, l3});
+}
+__device__ __forceinline__ void split_codes8(u32x4 w, f16x8& hi, f16x8& lo) { split_codes4(w.x, w.y, w.z, w.w, hi, lo); }
+
 // ------------------------------------------------------------------------------------------------
 // Decode attention.  Each wavefront walks its chunk of the plan above, segment by segment:
 //   S^T = K Q^T (keys x heads), online softmax per head along the key axis with cross-lane shuffles,
@@ -722,7 +788,8 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
 template <int HD, int G>
 __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __restrict__ q_hi, const uint16_t* __restrict__ q_lo,
                                                            const uint16_t* __restrict__ kplane,
-                                                           const uint16_t* __restrict__ vplane, const int32_t* __restrict__ seq_lens,
+                                                           const uint16_t* __restrict__ vplane, const float* __restrict__ kvscale,
+                                                           const int32_t* __restrict__ seq_lens,
                                                            const int32_t* __restrict__ table, int batch, int mbs, int Hq, int Hkv,
                                                            const int32_t* __restrict__ hdr, const int32_t* __restrict__ start,
                                                            int maxrec, float* __restrict__ part, uint16_t* __restrict__ xo, int MT) {
@@ -768,6 +835,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
 #pragma unroll
     for (int f = 0; f < NVF; ++f) oacc[f] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = NEG_INF, l_run = 0.f;
+    // The value scales ride on the probabilities (fp16 operands of the second product).  To keep those operands in
+    // fp16's normal range whatever the magnitude of the model's values, they are multiplied by a power of two taken
+    // from the first key's scale (2^-4 / 2^exponent, so p * scale * vnorm is about p / 16) and the accumulator is
+    // divided by it at the end of the segment.  Scales more than 2^11 times the first one would saturate.
+    float vnorm = 0.f, vnorm_inv = 0.f;
 
     // the segment in runs of at most 32 pairs = 64 blocks, whose ids are held one per lane
     for (int sp = 0; sp < np; sp += 32) {
@@ -780,12 +852,19 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
       struct KV {
         u32x4 k0[NKF], k1[NKF];
         u32x2 v0[NVF], v1[NVF];
+        f32x4 ks0, ks1, vs0, vs1;  // scales of this lane's keys 4g .. 4g+3 of the two blocks
       };
       auto load_pair = [&](KV& r, int pr) __attribute__((always_inline)) {
         const int id0 = __shfl(my_blk, min(2 * pr, last_blk_local));
         const int id1 = __shfl(my_blk, min(2 * pr + 1, last_blk_local));  // past the end: the last block again (masked)
         const int64_t off0 = ((int64_t)id0 * Hkv + j) * blk_elems;
         const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
+        const float* sc0 = kvscale + kv_scale_offset(id0, Hkv, j) + 4 * g;
+        const float* sc1 = kvscale + kv_scale_offset(id1, Hkv, j) + 4 * g;
+        r.ks0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(sc0));
+        r.vs0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(sc0 + 16));
+        r.ks1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(sc1));
+        r.vs1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(sc1 + 16));
 #pragma unroll
         for (int f = 0; f < NKF; ++f) {
           r.k0[f] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kplane + off0 + (f * 64 + lane) * 8));
@@ -799,52 +878,72 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
       };
       auto process = [&](KV& r, int pr) __attribute__((always_inline)) {
         const int base = k0 + pr * 32;
-        // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1)
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        // scores (already in log2 units): lane (head n, g) gets keys base + 4g + i (block 0) and base + 16 + 4g + i (block 1).
+        // Codes x = 256 a + b: the a plane meets both query planes, the b plane the hi plane (b q_lo is below 2^-19 of the score).
+        f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f}, b0 = {0.f, 0.f, 0.f, 0.f}, b1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int f = 0; f < NKF; ++f) {
-          s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qhi[f], s0, 0, 0, 0);
-          s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k0[f]), qlo[f], s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qhi[f], s1, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(r.k1[f]), qlo[f], s1, 0, 0, 0);
+          f16x8 ka, kb;
+          split_codes8(r.k0[f], ka, kb);
+          a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qhi[f], a0, 0, 0, 0);
+          a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qlo[f], a0, 0, 0, 0);
+          b0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb, qhi[f], b0, 0, 0, 0);
+          split_codes8(r.k1[f], ka, kb);
+          a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qhi[f], a1, 0, 0, 0);
+          a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qlo[f], a1, 0, 0, 0);
+          b1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb, qhi[f], b1, 0, 0, 0);
         }
-        float sc[8];
+        if (vnorm == 0.f) {  // first pair of the segment: its first key is valid, its scale sets the normaliser
+          const uint32_t bits = __builtin_amdgcn_readfirstlane(__float_as_uint(r.vs0[0]));
+          int e = (int)((bits >> 23) & 0xffu);
+          e = e < 8 ? 114 : min(e, 240);  // an all-zero first value vector: take 2^-13; (NaN / inf: anything finite)
+          vnorm = __uint_as_float((uint32_t)(250 - e) << 23);           // 2^(123 - e): scale * vnorm lies in [1/16, 1/8)
+          vnorm_inv = __uint_as_float((uint32_t)(e + 4) << 23);         // 2^(e - 123)
+        }
+        float sc[8], pvs[8];
         float mx = NEG_INF;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          sc[i] = (base + 4 * g + i < kend) ? s0[i] : NEG_INF;
-          sc[4 + i] = (base + 16 + 4 * g + i < kend) ? s1[i] : NEG_INF;
+          const bool ok0 = base + 4 * g + i < kend, ok1 = base + 16 + 4 * g + i < kend;
+          sc[i] = ok0 ? (a0[i] * 256.f + b0[i]) * r.ks0[i] : NEG_INF;
+          sc[4 + i] = ok1 ? (a1[i] * 256.f + b1[i]) * r.ks1[i] : NEG_INF;
+          pvs[i] = ok0 ? r.vs0[i] * vnorm : 0.f;      // slots past the end may hold anything: their scale never enters
+          pvs[4 + i] = ok1 ? r.vs1[i] * vnorm : 0.f;
           mx = fmaxf(mx, fmaxf(sc[i], sc[4 + i]));
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        // the probabilities go to the matrix cores as fp16 hi + lo, like every other operand of the single-token path
-        // (the kernel waits for memory, the second pass over the values costs nothing): one rounding site less per layer
-        union { uint16_t s[8]; f16x8 v; } pb, pl;
+        // the probabilities times the value scales go to the matrix cores as fp16 hi + lo, like every other operand of the
+        // single-token path (for the a plane of the value codes with the factor 256; the b plane, 2^-8 of the value, takes
+        // the hi part alone); non-negative, so one bound keeps a wild scale from overflowing
+        union { _Float16 s[8]; f16x8 v; } pa, pl, pb;
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          float pv = __builtin_amdgcn_exp2f(sc[i] - m_new);
+          const float pv = __builtin_amdgcn_exp2f(sc[i] - m_new);
           psum += pv;
-          split_f16(pv, pb.s[i], pl.s[i]);
+          const float w = fminf(pv * pvs[i], 255.f), w256 = w * 256.f;
+          pa.s[i] = (_Float16)w256;
+          pl.s[i] = (_Float16)(w256 - (float)pa.s[i]);
+          pb.s[i] = (_Float16)w;
         }
         l_run = l_run * alpha + psum;
         m_run = m_new;
-        // values of masked keys must not reach the MFMA (0 * NaN): clear them.  Done for every pair, without a branch:
-        // the masks are all-ones except in a sequence's last pair.
-        const int ka = base + 4 * g, kb2 = base + 16 + 4 * g;
-        const uint32_t a01 = (ka + 0 < kend ? 0xFFFFu : 0u) | (ka + 1 < kend ? 0xFFFF0000u : 0u);
-        const uint32_t a23 = (ka + 2 < kend ? 0xFFFFu : 0u) | (ka + 3 < kend ? 0xFFFF0000u : 0u);
-        const uint32_t b01 = (kb2 + 0 < kend ? 0xFFFFu : 0u) | (kb2 + 1 < kend ? 0xFFFF0000u : 0u);
-        const uint32_t b23 = (kb2 + 2 < kend ? 0xFFFFu : 0u) | (kb2 + 3 < kend ? 0xFFFF0000u : 0u);
+        if (__any(alpha != 1.f)) {  // the running maximum moved for some head of the wavefront (rare after the first pairs)
+#pragma unroll
+          for (int f = 0; f < NVF; ++f) {
+            oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
+          }
+        }
 #pragma unroll
         for (int f = 0; f < NVF; ++f) {
-          const u32x4 a = {r.v0[f].x & a01, r.v0[f].y & a23, r.v1[f].x & b01, r.v1[f].y & b23};
-          oacc[f][0] *= alpha; oacc[f][1] *= alpha; oacc[f][2] *= alpha; oacc[f][3] *= alpha;
-          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pb.v, oacc[f], 0, 0, 0);
-          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), pl.v, oacc[f], 0, 0, 0);
+          f16x8 va, vb;
+          split_codes4(r.v0[f].x, r.v0[f].y, r.v1[f].x, r.v1[f].y, va, vb);
+          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pa.v, oacc[f], 0, 0, 0);
+          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pl.v, oacc[f], 0, 0, 0);
+          oacc[f] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vb, pb.v, oacc[f], 0, 0, 0);
         }
       };
 
@@ -873,6 +972,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const uint16_t* __rest
 
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+    for (int f = 0; f < NVF; ++f) {
+      oacc[f][0] *= vnorm_inv; oacc[f][1] *= vnorm_inv; oacc[f][2] *= vnorm_inv; oacc[f][3] *= vnorm_inv;
+    }
 
     const int S = x - p;                // list position of this (b, j) sequence's first pair
     const int first_w = S / C;
@@ -1156,13 +1259,14 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
     const LayerW& w = m->layers[l];
     uint16_t* kplane = (uint16_t*)m->kv + (int64_t)(2 * l) * m->kv_plane;
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
+    float* kvscale = m->kv_scales + (int64_t)l * m->kv_scale_plane;
     {
       GemmP p = {};
       p.W = (const u32x4*)(w.wqkv8 ? (const void*)w.wqkv8 : (const void*)w.wqkv); p.Wlo = (const u32x4*)w.wqkv_lo; p.wfactor = w.sqkv; p.Wscale = (const u32x2*)w.gqkv;
       p.NRG = m->QKVN / 16; p.KB = d / 32;
       p.X = (const u32x4*)m->xq; p.M = batch;
       p.ssq_in = m->ssq; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
-      p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
+      p.q_hi = m->q_hi; p.q_lo = m->q_lo; p.qscale = qscale; p.kplane = kplane; p.vplane = vplane; p.kvscale = kvscale; p.seq_lens = lens; p.table = table; p.mbs = m->cfg.max_blocks_per_seq;
       p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope; p.qk_gain = w.qk_gain;
       prof_mark(m, PK_QKV, st);
       launch_gemm<EPI_QKV>(m, p, MT, st);
@@ -1172,7 +1276,7 @@ int run_decode(www_model* m, const int32_t* tok, const int32_t* lens, const int3
 #define ATTN(HD_, G_)                                                                                                              \
   {                                                                                                                                \
     hipLaunchKernelGGL((decode_attn_kernel<HD_, G_>), dim3(m->attn_waves / 4), dim3(256), 0, st, m->q_hi, m->q_lo, kplane, vplane,  \
-                       lens, table, batch, (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_hdr, m->attn_start,            \
+                       kvscale, lens, table, batch, (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, m->attn_hdr, m->attn_start,            \
                        m->attn_maxrec,                                                                                             \
                        m->attn_part, (uint16_t*)m->xo, MT);                                                                        \
     hipLaunchKernelGGL((decode_attn_merge_kernel<HD_, G_>), dim3(m->Hkv, batch), dim3(64), 0, st, lens, m->Hkv, m->attn_hdr,        \

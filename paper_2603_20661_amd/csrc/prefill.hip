@@ -121,7 +121,8 @@ struct PGemmP {
   // QKV epilogue
   const float* qk_gain;  // models with normalised query / key heads: [2][hd] gains in packed row order; null otherwise
   uint16_t* qp;
-  uint16_t *kplane, *vplane;
+  uint16_t *kplane, *vplane;  // this layer's key / value planes of the pool (16-bit codes)
+  float* kvscale;             // and its plane of scales
   const int32_t *row_seq, *row_pos, *table;
   int mbs, hd, Hq, Hkv;
   const float2* rope;
@@ -413,6 +414,44 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
         head_rs[hh] = rsqrtf(ss[hh] / (float)p.hd + p.eps);
       }
     }
+    // QKV: finish the values in place (RMSNorm factor, head normalisation, rotation) and take the largest magnitude of
+    // each head's vector for this token: the scale of its key / value codes.  A wavefront's 128 rows are one head of
+    // 128 or two of 64 (row blocks 0,1 and 2,3); the token's values sit in the lanes l and l + 32.
+    float head_amax[2] = {0.f, 0.f};
+    if constexpr (EPI == PEPI_QKV) {
+      const int rot_rows = (p.Hq + p.Hkv) * p.hd;
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int rg = rg_tile + wn * 8 + rb * 2 + (q4 >> 1);
+          const int n0 = rg * 16 + (q4 & 1) * 8 + hsel * 4;
+          float v4[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i] * scale[tb];
+          if (n0 < rot_rows) {
+            if constexpr (QKN) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v4[i] *= head_rs[rb >> 1] * gv[rb][q4][i];
+            }
+            const f32x4 cs = pre[rb][q4];  // (cos, sin) of the two rotary pairs held here
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+              float a = v4[2 * pr], b = v4[2 * pr + 1];
+              v4[2 * pr] = a * cs[2 * pr] - b * cs[2 * pr + 1];
+              v4[2 * pr + 1] = b * cs[2 * pr] + a * cs[2 * pr + 1];
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[rb][tb][q4 * 4 + i] = v4[i];
+            head_amax[rb >> 1] = fmaxf(head_amax[rb >> 1], __builtin_fabsf(v4[i]));
+          }
+        }
+      if (p.hd == 128) head_amax[0] = head_amax[1] = fmaxf(head_amax[0], head_amax[1]);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) head_amax[hh] = fmaxf(head_amax[hh], __shfl_xor(head_amax[hh], 32));
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {
@@ -450,35 +489,30 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
               o.s[i] = f32_to_f16_sat(hn[i] * g4[i]);
             }
             *reinterpret_cast<u32x2*>(p.xn_out + packed_p_offset(t, n0, p.d >> 4)) = o.v;
-          } else {  // PEPI_QKV
-            const int rot_rows = (p.Hq + p.Hkv) * p.hd;
+          } else {  // PEPI_QKV: the values were finished in place above
             const int head = n0 / p.hd, c0 = n0 % p.hd;
-            if (n0 < rot_rows) {
-              if constexpr (QKN) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v4[i] *= head_rs[rb >> 1] * gv[rb][q4][i];
-              }
-              const f32x4 cs = pre[rb][q4];  // (cos, sin) of the two rotary pairs held here
-#pragma unroll
-              for (int pr = 0; pr < 2; ++pr) {
-                float a = v4[2 * pr], b = v4[2 * pr + 1];
-                v4[2 * pr] = a * cs[2 * pr] - b * cs[2 * pr + 1];
-                v4[2 * pr + 1] = b * cs[2 * pr] + a * cs[2 * pr + 1];
-              }
-            }
+            for (int i = 0; i < 4; ++i) v4[i] = acc[rb][tb][q4 * 4 + i];
             union { uint16_t s[4]; u32x2 v; } o;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(v4[i]);  // q, k, v feed the fp16 attention kernels
             if (head < p.Hq) {
-              *reinterpret_cast<u32x2*>(p.qp + (int64_t)t * (p.Hq * p.hd) + n0) = o.v;
-            } else if (head < p.Hq + p.Hkv) {
-              const int j = head - p.Hq;
-              *reinterpret_cast<u32x2*>(p.kplane + (kvbase + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = o.v;
-            } else {
-              const int j = head - p.Hq - p.Hkv;
-              uint16_t* dst = p.vplane + (kvbase + j) * (int64_t)(KV_BS * p.hd);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) dst[v_cache_offset(tok, c0 + i)] = o.s[i];
+              for (int i = 0; i < 4; ++i) o.s[i] = f32_to_f16_sat(v4[i]);  // queries feed the fp16 attention kernel
+              *reinterpret_cast<u32x2*>(p.qp + (int64_t)t * (p.Hq * p.hd) + n0) = o.v;
+            } else {
+              // keys and values go to the cache as 16-bit codes with the scale of their (token, head) vector
+              const bool is_v = head >= p.Hq + p.Hkv;
+              const int j = head - p.Hq - (is_v ? p.Hkv : 0);
+              const float amax = head_amax[rb >> 1], inv = kv_code_inv(amax);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) o.s[i] = kv_code(v4[i], inv);
+              if (!is_v) {
+                *reinterpret_cast<u32x2*>(p.kplane + (kvbase + j) * (int64_t)(KV_BS * p.hd) + k_cache_offset(tok, c0)) = o.v;
+              } else {
+                uint16_t* dst = p.vplane + (kvbase + j) * (int64_t)(KV_BS * p.hd);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dst[v_cache_offset(tok, c0 + i)] = o.s[i];
+              }
+              if (c0 == 0) p.kvscale[kv_scale_offset(slot / KV_BS, p.Hkv, j) + (is_v ? 16 : 0) + tok] = kv_code_scale(amax);
             }
           }
         }
@@ -502,13 +536,16 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 // sequence x one kv head (x GH of its query heads); each wavefront owns 16 query positions and keeps
 // S^T = K Q^T / O^T = V^T P^T for its GH heads.  The keys and values of a pair of blocks (32 keys) are
 // copied into LDS once per workgroup and read from there by the four wavefronts (the cache already stores them
-// in MFMA operand order, so the copy is verbatim); the next pair travels from memory while this one is used.
+// in MFMA operand order; the copy turns the 16-bit codes into fp16 values, code * scale of its token, rounded once - the
+// precision an fp16 cache would give this pass, which only needs the keys and values of other positions to matrix-core
+// accuracy); the next pair travels from memory while this one is used.
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 template <int HD, int GH>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
-                                                            const uint16_t* __restrict__ vplane, const int32_t* __restrict__ q_lens,
+                                                            const uint16_t* __restrict__ vplane, const float* __restrict__ kvscale,
+                                                            const int32_t* __restrict__ q_lens,
                                                             const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ table,
                                                             int mbs, int Hq, int Hkv, int G, const int32_t* __restrict__ tile_seq,
                                                             const int32_t* __restrict__ tile_q0, const int32_t* __restrict__ meta,
@@ -560,6 +597,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
 
   const int64_t blk_elems = (int64_t)KV_BS * HD;
   u32x4 stg[NLD];
+  // units 0 .. NLD/2-1 of a thread are keys (one token per unit: one scale), the others values (four tokens per unit)
+  static_assert(NLD % 2 == 0 && (NLD / 2) * 256 == 2 * CH, "the first half of a thread's units are keys");
+  float ksc[NLD / 2];
+  f32x4 vsc[NLD / 2];
   // Block ids are fetched one pair ahead of the request that uses them, so the request never waits for the table.
   // A pair past the workgroup's last one is redirected to the last one (in bounds, never used).
   int id0 = 0, id1 = 0;
@@ -576,11 +617,28 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
       const int u = tid + i * 256, c = u / CH, within = u % CH;
       const uint16_t* src = (c < 2 ? kplane : vplane) + ((c & 1) ? off1 : off0) + within * 8;
       stg[i] = *reinterpret_cast<const u32x4*>(src);
+      const float* sc = kvscale + kv_scale_offset((c & 1) ? id1 : id0, Hkv, j);
+      if (i < NLD / 2) ksc[i] = sc[within & 15];                                        // key unit: token = unit % 16
+      else vsc[i - NLD / 2] = *reinterpret_cast<const f32x4*>(sc + 16 + ((within >> 3) & 3) * 4);  // value unit: tokens 4t .. 4t+3
     }
   };
   auto copy_in = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) kv[buf][tid + i * 256] = stg[i];
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t w[4] = {stg[i].x, stg[i].y, stg[i].z, stg[i].w};
+      u32x4 out;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        // word d holds elements 2d, 2d+1 of the unit; a value unit's element e belongs to token e % 4
+        const float s0 = i < NLD / 2 ? ksc[i < NLD / 2 ? i : 0] : vsc[i < NLD / 2 ? 0 : i - NLD / 2][(2 * d) & 3];
+        const float s1 = i < NLD / 2 ? ksc[i < NLD / 2 ? i : 0] : vsc[i < NLD / 2 ? 0 : i - NLD / 2][(2 * d + 1) & 3];
+        // offset-binary codes u = q + 32768:  value = (u - 32768) * scale
+        const float x0 = __builtin_fmaf((float)(w[d] & 0xffffu), s0, -32768.f * s0), x1 = __builtin_fmaf((float)(w[d] >> 16), s1, -32768.f * s1);
+        const f16x2 h = __builtin_convertvector((f32x2){x0, x1}, f16x2);
+        out[d] = __builtin_bit_cast(uint32_t, h);
+      }
+      kv[buf][tid + i * 256] = out;
+    }
   };
   // masked = false: every key of the pair is visible to every query of the wavefront (the pair ends at or before its
   // first query position), so neither the scores nor the values need a mask; that is the case for all pairs but the
@@ -745,7 +803,7 @@ static void launch_pgemm(PGemmP& p, hipStream_t st) {
 }
 
 template <int HD>
-static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* vplane, const int32_t* qlens, const int32_t* lens,
+static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* vplane, const float* kvscale, const int32_t* qlens, const int32_t* lens,
                          const int32_t* table, int max_tiles, hipStream_t st) {
   const int G = m->G;
   // two query heads per workgroup pass: their accumulators and operands fit 256 registers, so two workgroups share a
@@ -755,7 +813,8 @@ static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* v
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const int32_t* cum_rows = m->meta + 16;
 #define PATTN(GH_)                                                                                                                 \
-  hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, qlens, lens, table, \
+  hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, kvscale, qlens, lens, \
+                     table,                                                                                                        \
                      (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, G, m->tile_seq, m->tile_q0, m->meta, cum_rows, scale_log2,      \
                      (uint16_t*)m->op)
   if (GH == 4) PATTN(4); else if (GH == 2) PATTN(2); else PATTN(1);
@@ -781,17 +840,18 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     const LayerW& w = m->layers[l];
     uint16_t* kplane = (uint16_t*)m->kv + (int64_t)(2 * l) * m->kv_plane;
     uint16_t* vplane = (uint16_t*)m->kv + (int64_t)(2 * l + 1) * m->kv_plane;
+    float* kvscale = m->kv_scales + (int64_t)l * m->kv_scale_plane;
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wqkv; p.wfactor = w.sqkv; p.NRG = m->QKVN / 16; p.KB = d / 32; p.X = (const u32x4*)m->xn; p.T = T;
       p.ssq_in = m->ssq_p; p.n_ssq_in = n_ssq; p.inv_dim = 1.f / d; p.eps = m->cfg.rms_eps;
-      p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
+      p.qp = (uint16_t*)m->qp; p.kplane = kplane; p.vplane = vplane; p.kvscale = kvscale; p.row_seq = m->row_seq; p.row_pos = m->row_pos; p.table = table;
       p.mbs = m->cfg.max_blocks_per_seq; p.hd = m->hd; p.Hq = m->Hq; p.Hkv = m->Hkv; p.rope = m->rope; p.qk_gain = w.qk_gain;
       launch_pgemm<PEPI_QKV>(p, st);
     }
     if (l == m->L - 1) break;  // only this layer's keys and values are still needed
-    if (m->hd == 128) launch_pattn<128>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
-    else launch_pattn<64>(m, kplane, vplane, qlens, lens, table, max_tiles, st);
+    if (m->hd == 128) launch_pattn<128>(m, kplane, vplane, kvscale, qlens, lens, table, max_tiles, st);
+    else launch_pattn<64>(m, kplane, vplane, kvscale, qlens, lens, table, max_tiles, st);
     {
       PGemmP p = {};
       p.W = (const u32x4*)w.wo; p.wfactor = w.so; p.NRG = d / 16; p.KB = m->QD / 32; p.X = (const u32x4*)m->op; p.T = T;

@@ -54,17 +54,17 @@ def duel_prompts():
     return synth.tokens(12345, DUEL["n_seq"] * DUEL["plen"], 32000).reshape(DUEL["n_seq"], DUEL["plen"])
 
 
-MIXED = dict(n_seq=128, chunk=512, budget=8192, dec_steps=64, zipf_seed=2, sample_len=525)
+MIXED = dict(n_seq=128, chunk=512, budget=8192, dec_steps=64, zipf_seed=2, sample_lens=(525, 546))
 
 
 def mixed_case():
-    """(lens, prompts, sampled sequence id) of the long-context mixed batch: the sampled sequence is the one of 525
-    tokens, whose prompt is fed in two chunks."""
+    """(lens, prompts, sampled sequence ids) of the long-context mixed batch: the sampled sequences are the ones of 525
+    and 546 tokens, whose prompts are fed in two chunks."""
     m = MIXED
     lens = synth.lengths_zipf(m["zipf_seed"], m["n_seq"], 1.2, 256, 16384).astype(np.int64)
     prompts = [synth.tokens(1000 + b, int(lens[b]), synth.M8B.vocab) for b in range(m["n_seq"])]
-    b = int(np.nonzero(lens == m["sample_len"])[0][0])
-    return lens, prompts, b
+    ids = [int(np.nonzero(lens == n)[0][0]) for n in m["sample_lens"]]
+    return lens, prompts, ids
 
 
 # ------------------------------------------------------------------ stored results

@@ -66,14 +66,15 @@ def main():
         C.pack_rows("judge", lg, out["cols"], out)
         out["judge_in"] = judge_in
     elif case == "mixed":
-        lens, prompts, b = C.mixed_case()
+        lens, prompts, ids = C.mixed_case()
         shape = synth.M8B
         cols = C.sample_columns(shape.vocab, 3)
         blob = synth.make_blob(shape)
-        log(f"mixed batch: sequence {b} of {int(lens[b])} tokens in chunks of {C.MIXED['chunk']}")
-        lg = greedy(shape, blob, [prompts[b]], C.MIXED["dec_steps"], chunk=C.MIXED["chunk"])[0]
-        out["cols"], out["seq_ids"] = cols, np.array([b], np.int32)
-        C.pack_rows(f"seq{b}", lg, cols, out)
+        log(f"mixed batch: sequences {ids} of {[int(lens[b]) for b in ids]} tokens in chunks of {C.MIXED['chunk']}")
+        logits = greedy(shape, blob, [prompts[b] for b in ids], C.MIXED["dec_steps"], chunk=C.MIXED["chunk"])
+        out["cols"], out["seq_ids"] = cols, np.array(ids, np.int32)
+        for b, lg in zip(ids, logits):
+            C.pack_rows(f"seq{b}", lg, cols, out)
     else:
         raise SystemExit(f"unknown case {case}")
     np.savez(C.golden_path(case), **out)

@@ -29,7 +29,7 @@ def test_query_sizes_and_config_validation():
     cfg = B.make_config(synth.M8B, 64, 272, 81920, 6000)
     wbytes, kvbytes, wsbytes = B.www_query_sizes(cfg)
     assert wbytes == synth.blob_layout(synth.M8B)[1]
-    assert kvbytes == 6000 * 32 * 2 * 8 * 16 * 128 * 2          # 2 MiB per block for the 8B shape
+    assert kvbytes == 6000 * 32 * 2 * 8 * 16 * (128 * 2 + 4)    # 2 MiB of 16-bit codes + 32 KiB of scales per block for the 8B shape
     # the blob of every source format, with and without the gains of the head normalisation, is as long as the generator's
     import dataclasses
     for base in (synth.M8B, synth.M1B, synth.TINY):

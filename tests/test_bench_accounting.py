@@ -15,7 +15,7 @@ def test_decode_step_bytes_are_the_streamed_tensors_plus_the_context():
     B = len(ctx)
     entries, _ = synth.blob_layout(SHAPE)
     weights = sum(rows * cols * 2 for name, _, rows, cols, dt in entries if dt == synth.WDTYPE_BF16 and name != "embed")
-    kv_token = SHAPE.n_layers * 2 * SHAPE.n_kv_heads * SHAPE.head_dim * 2
+    kv_token = SHAPE.n_layers * 2 * SHAPE.n_kv_heads * (SHAPE.head_dim * 2 + 4)      # 16-bit codes and one fp32 scale per vector
     want = weights + B * SHAPE.d_model * 2 + int(ctx.sum()) * kv_token + B * kv_token + B * SHAPE.vocab * 4
     assert bench.decode_step_bytes(SHAPE, ctx, B) == want
 

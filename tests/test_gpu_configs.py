@@ -230,13 +230,13 @@ def test_duel_and_judge_round(depth):
 def test_long_context_mixed_batch_interleaved_schedule(depth):
     """128 sequences with Zipf(1.2) lengths up to 15 650 tokens on the 8B-shaped model: prefill calls of 512-token chunks
     under an 8192-token budget interleaved with decode steps (batches of changing composition), block tables scattered
-    over a pool of 90 % of the free device memory.  Full depth: the 525-token sequence (two chunks, 64 decode steps)
-    against the stored oracle rows.  Two layers: the shortest, the median and a 3013-token sequence against the oracle
+    over a pool of 90 % of the free device memory.  Full depth: the 525- and the 546-token sequence (two chunks, 64 decode
+    steps each) against the stored oracle rows.  Two layers: the shortest, the median and a 3013-token sequence against the oracle
     on the spot."""
     import torch
     from paper_2603_20661_amd import binding as B
     m = C.MIXED
-    lens, prompts, b_full = C.mixed_case()
+    lens, prompts, ids_full = C.mixed_case()
     full = depth == "full"
     shape = synth.M8B if full else WIDE8B
     n_seq, chunk, budget, dec_steps = m["n_seq"], m["chunk"], m["budget"], m["dec_steps"]
@@ -244,7 +244,8 @@ def test_long_context_mixed_batch_interleaved_schedule(depth):
     mbs = int((cap.max() + 15) // 16)
     blob = synth.make_blob(shape, gain_std=0.0 if full else 0.05)
     if full:
-        oracle_rows = {b_full: C.Stored(load("mixed"), f"seq{b_full}")}
+        z = load("mixed")
+        oracle_rows = {b: C.Stored(z, f"seq{b}") for b in ids_full if f"seq{b}.tokens" in z}
     else:
         order = np.argsort(lens)
         sample = [int(order[0]), int(order[n_seq // 2]), int(order[np.searchsorted(lens[order], 3000)])]
@@ -254,11 +255,15 @@ def test_long_context_mixed_batch_interleaved_schedule(depth):
     torch.cuda.synchronize()
     torch.cuda.empty_cache()                      # what earlier tests left in the allocator's cache is not "free" otherwise
     free_bytes, _ = torch.cuda.mem_get_info()
-    block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * shape.head_dim * 2
+    block_bytes = shape.n_layers * 2 * shape.n_kv_heads * 16 * (shape.head_dim * 2 + 4)
     nb = int(0.90 * (free_bytes - ws_bytes - blob.nbytes)) // block_bytes
     table = synth.block_tables(2, cap, nb, mbs, permute=True)
     used = table[table >= 0]
-    assert int(used.max()) * (16 * shape.n_kv_heads * shape.head_dim) > 2 ** 32, "the pool must reach past 32-bit element offsets"
+    # two layers: 1.9 M blocks, so that offsets inside one layer's key or value plane pass 32 bits; full depth: 115 000 blocks
+    # of 2 MiB, whose planes lie up to 2^37 bytes into the pool
+    plane = nb * 16 * shape.n_kv_heads * shape.head_dim
+    assert (int(used.max()) * (16 * shape.n_kv_heads * shape.head_dim) if not full else plane * 2 * shape.n_layers) > 2 ** 32, \
+        "the pool must reach past 32-bit element offsets"
     sess = GpuSession(shape, blob, n_seq, mbs * 16, budget, nb)
     rows = {b: [] for b in oracle_rows}
     try:

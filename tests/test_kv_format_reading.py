@@ -1,10 +1,14 @@
-"""Why the KV cache and the matrix-core operands are IEEE fp16 and not bf16 (both are 16 bits wide and run at the same
-matrix-core rate): measured with the oracle alone.  The 16-layer 1B-shaped model prefills four prompts of 256 tokens; from there three
-copies of the cache are decoded side by side, one exact (fp32, the oracle's own), one rounded to bf16 after every call
-and one rounded to fp16 after every call - nothing else differs.  With bf16 storage the logits alone leave the 3e-2
-tolerance that the GPU path as a whole has to hold; with fp16 storage they stay an order of magnitude inside it.
-The rounding itself is the library conversion of PyTorch (round to nearest even), not code of the oracle or of the GPU
-path."""
+"""Why the matrix-core operands are IEEE fp16 and not bf16, and why the KV cache holds 16-bit integer codes with one
+scale per (token, head) vector rather than fp16 or bf16 numbers (all are 16 bits per element): measured with the oracle
+alone.  The 16-layer 1B-shaped model prefills four prompts of 256 tokens; from there four copies of the cache are decoded
+side by side, one exact (fp32, the oracle's own) and three passed through a 16-bit storage format after every call -
+bf16, fp16, scaled integer codes - nothing else differs.  With bf16 storage the logits alone leave the 3e-2 tolerance
+that the GPU path as a whole has to hold; fp16 storage stays an order of magnitude inside it (but at 32 layers and a
+vocabulary of 128 256 it alone moves the logits by 1.4e-2, enough to flip more than 1 % of the greedy tokens of a
+random-initialised model); the integer codes are several times finer again.
+The fp16 / bf16 rounding is the library conversion of PyTorch (round to nearest even), the codes are written out here
+(q = round(x / s), s = max|x| / 32767 over the head_dim values of one token and head): none of it is code of the oracle
+or of the GPU path."""
 import numpy as np
 import pytest
 import torch
@@ -16,10 +20,18 @@ TOL = 3e-2
 
 
 def rounded(a: np.ndarray, dtype) -> np.ndarray:
+    if dtype == "codes":                      # a: [..., Hkv * hd]; one scale per (token, head) vector of HD values
+        v = a.reshape(-1, HD)
+        s = np.abs(v).max(-1, keepdims=True) / 32767.0
+        s[s == 0] = 1.0
+        return (np.rint(v / s) * s).astype(np.float32).reshape(a.shape)
     return torch.from_numpy(a).to(dtype).float().numpy()
 
 
-def test_bf16_kv_storage_alone_breaks_the_tolerance_and_fp16_does_not():
+HD = synth.M1B.head_dim
+
+
+def test_bf16_kv_storage_alone_breaks_the_tolerance_fp16_does_not_and_scaled_codes_are_finer_still():
     shape = synth.M1B
     blob = synth.make_blob(shape)
     n_seq, plen, steps = 4, 256, 6
@@ -30,7 +42,8 @@ def test_bf16_kv_storage_alone_breaks_the_tolerance_and_fp16_does_not():
     table = synth.block_tables(5, [cap] * n_seq, nb, mbs)
     lens = np.full(n_seq, plen, np.int32)
     exact = O.OracleModel(shape, blob, num_blocks=nb)
-    variants = {"bf16": (O.OracleModel(shape, blob, num_blocks=nb), torch.bfloat16), "fp16": (O.OracleModel(shape, blob, num_blocks=nb), torch.float16)}
+    variants = {"bf16": (O.OracleModel(shape, blob, num_blocks=nb), torch.bfloat16), "fp16": (O.OracleModel(shape, blob, num_blocks=nb), torch.float16),
+                "codes": (O.OracleModel(shape, blob, num_blocks=nb), "codes")}
     try:
         _, nxt, _ = exact.forward(toks, lens, lens, block_table=table)
         for m, dt in variants.values():              # the same prefill, its cache rounded to the storage format
@@ -44,10 +57,12 @@ def test_bf16_kv_storage_alone_breaks_the_tolerance_and_fp16_does_not():
                 m.kv_paged()[:] = rounded(m.kv_paged().copy(), dt)
                 worst[k] = max(worst[k], float(np.abs(got - ref).max()))
             nxt = nxt_new
-        print(f"KV storage alone, 1B shape, {n_seq} x {plen} tokens + {steps} steps: max|dlogit| bf16 {worst['bf16']:.3e}, fp16 {worst['fp16']:.3e}")
+        print(f"KV storage alone, 1B shape, {n_seq} x {plen} tokens + {steps} steps: max|dlogit| bf16 {worst['bf16']:.3e}, fp16 {worst['fp16']:.3e}, "
+              f"16-bit codes {worst['codes']:.3e}")
         assert worst["bf16"] > TOL, worst
         assert worst["fp16"] < TOL / 4, worst
         assert worst["bf16"] > 6 * worst["fp16"], worst       # three more significant bits: a factor of eight, give or take
+        assert worst["fp16"] > 3 * worst["codes"], worst
     finally:
         exact.close()
         for m, _ in variants.values():
