@@ -49,49 +49,57 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 CALIB_COPY_BYTES = 1 << 28  # size of the counter-calibration copy
 
-# HBM traffic of the dominant decode kernel class (decode_attn_kernel + decode_attn_merge_kernel), from two
-# `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE; profiles/decode_attention_8b_traffic.md).
-# Counter units per launch, averaged over the 256 launches of those runs; scale = bytes per unit / 1024, from what the
-# same counter read for the calibration copy above (131 088.8 units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units
-# of WRITE_SIZE for 262 144 KiB written); algorithmic bytes of those same launches for rescaling to another context.
-# Valid only for the kernels it was taken with: the hash covers the text of the attention plan / attention / merge kernels
-# in decode.hip and of the layout helpers in common.h; the reading is reported as null when that text has changed.
+# HBM traffic of the decode kernel classes, from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then WRITE_SIZE;
+# profiles/decode_kernels_8b_traffic.md).  Counter units per launch, averaged over the 256 launches per class of those runs
+# (8 for the output head); scale = KiB per unit, from what the same counter read for the calibration copy above (131 087.1
+# units of FETCH_SIZE for 262 144 KiB read, 262 144.0 units of WRITE_SIZE for 262 144 KiB written).  The attention
+# reading is rescaled linearly to the reported launch's context (its traffic is proportional to it); the GEMMs' bytes do
+# not depend on the step.  Valid only for the kernels it was taken with: the hash covers the text of decode.hip and
+# common.h; every reading is reported as null when that text has changed.
 TRAFFIC = {
-    "workload": "8b", "kernel": "decode_attention",
-    "fetch_units": 162676.4 + 1672.4, "write_units": 3107.9 + 1024.0,
-    "fetch_scale": 262144.0 / 131088.8, "write_scale": 1.0,
-    "algorithmic_bytes_of_measured_launches": 80383 * 4096,
-    "sources": (("paper_2603_20661_amd/csrc/decode.hip", "// Plan of the decode attention", "void argmax_take("),
-                ("paper_2603_20661_amd/csrc/common.h", "inline int64_t packed_w_elems(", "struct LayerW {")),
-    "sha256": "dc3bc565fb80e21f5e3c66b4e97af4d8851cfe3cc53f9865f773c83170ebf23a",
+    "workload": "8b",
+    "fetch_scale": 262144.0 / 131087.1, "write_scale": 1.0,
+    "classes": {   # class: (FETCH_SIZE units, WRITE_SIZE units, algorithmic bytes of the measured launches or None = this run's)
+        "decode_attention": (165304.6 + 1669.0, 3107.2 + 1024.0, 80383 * 4160),
+        "qkv_gemm": (32960.2, 9513.0, None),
+        "o_gemm": (25222.0, 10313.0, None),
+        "gate_up_gemm": (118939.6, 3584.0, None),
+        "down_gemm": (76424.4, 10313.0, None),
+        "lm_head_gemm": (529392.8, 32068.2, None),
+    },
+    "sources": ("paper_2603_20661_amd/csrc/decode.hip", "paper_2603_20661_amd/csrc/common.h"),
+    "sha256": "342b09e6dd9f9cefa0e384a9223eea53e53d2bd049cfa55c14bb3eb7a7807254",
 }
 
 
 def kernel_text_hash():
-    """sha256 over the source text of the measured kernels (from a start marker up to an end marker in each file)"""
+    """sha256 over the source text of the measured kernels"""
     import hashlib
     h = hashlib.sha256()
-    for f, start, end in TRAFFIC["sources"]:
-        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), f), "r") as fh:
-            text = fh.read()
-        a = text.index(start)
-        h.update(text[a:text.index(end, a)].encode())
+    for f in TRAFFIC["sources"]:
+        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), f), "rb") as fh:
+            h.update(fh.read())
     return h.hexdigest()
 
 
 def measured_traffic(workload, kernel, algorithmic_bytes_per_launch):
-    """HBM bytes per launch of `kernel` from the stored counter readings, rescaled linearly to this launch's algorithmic
-    bytes (attention traffic is proportional to the context); None if there is no reading for this workload / kernel or the
-    kernel sources have changed since it was taken."""
-    if workload != TRAFFIC["workload"] or kernel != TRAFFIC["kernel"]:
+    """HBM bytes per launch of a decode kernel class from the stored counter readings (the attention class rescaled
+    linearly to this launch's algorithmic bytes); None if there is no reading for this workload / class or the kernel
+    sources have changed since it was taken."""
+    if workload != TRAFFIC["workload"] or kernel not in TRAFFIC["classes"]:
         return None
     try:
         if kernel_text_hash() != TRAFFIC["sha256"]:
             return None
-    except (OSError, ValueError):
+    except OSError:
         return None
-    measured = (TRAFFIC["fetch_units"] * TRAFFIC["fetch_scale"] + TRAFFIC["write_units"] * TRAFFIC["write_scale"]) * 1024.0
-    return int(round(measured * algorithmic_bytes_per_launch / TRAFFIC["algorithmic_bytes_of_measured_launches"]))
+    fetch, write, alg_measured = TRAFFIC["classes"][kernel]
+    measured = (fetch * TRAFFIC["fetch_scale"] + write * TRAFFIC["write_scale"]) * 1024.0
+    if alg_measured:
+        measured *= algorithmic_bytes_per_launch / alg_measured
+    return int(round(measured))
+
+
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
 
 
@@ -550,7 +558,8 @@ def main():
                 avg = ms / n
                 gbs = per_bytes[k] / (avg * 1e-3) / 1e9
                 kernels[k] = {"launches_per_step": n // nprof, "avg_ms": round(avg, 5), "GBps": round(gbs, 1),
-                              "ms_per_step": round(ms / nprof, 4)}
+                              "ms_per_step": round(ms / nprof, 4), "frac": round(gbs / HBM_PEAK_GBS, 4),
+                              "algorithmic_bytes": int(per_bytes[k]), "traffic": measured_traffic(args.workload, k, per_bytes[k])}
     assert np.isfinite(logits.cpu().numpy()).all(), "non-finite logits"
 
     dec_tok_s = Bn * nsteps * args.steps / (dec_ms * 1e-3) if nsteps else 0.0
