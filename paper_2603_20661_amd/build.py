@@ -12,6 +12,7 @@ LIB = os.path.join(HERE, "libwww.so")
 SOURCES = ["api.hip", "pack.hip", "decode.hip", "prefill.hip", "duel.hip", "sample.hip", "probe.hip", "sched.cpp", "ledger.cpp"]   # the .cpp files are host-only C++
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+         "-Wno-inline-asm",   # the LDS-copy assembly names M0 as clobbered, which clang reports as a reserved register
          "-fvisibility=hidden", "-fvisibility-inlines-hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -109,7 +109,8 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const int32_t* __restri
 // fragment order (packed weights, packed activations), so a K step of 32 is a straight 32 KiB copy into
 // LDS (16 weight fragments + 16 activation fragments) and every LDS read is a conflict-free 16-byte read.
 enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_SWIGLU = 2 };
-#define PGEMM_LDS_BYTES (3 * 2048 * 16)
+#define PGEMM_NB 4  // stage buffers of the prefill GEMM (32 KiB each)
+#define PGEMM_LDS_BYTES (PGEMM_NB * 2048 * 16)
 
 struct PGemmP {
   const u32x4* W;  // packed weights
@@ -145,7 +146,7 @@ struct PGemmP {
 // kernel carries none of its registers)
 template <int EPI, bool QKN = false>
 __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
-  // three stage buffers of 2048 sixteen-byte units: 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
+  // PGEMM_NB stage buffers of 2048 sixteen-byte units: 0..1023 weights [16 row groups][64], 1024..2047 activations [8 token groups][2 k16][64]
   extern __shared__ u32x4 smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
@@ -174,127 +175,111 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // global source of this thread's 4 + 4 staging units (they advance by one k block per stage)
+  // Stage copies go from memory straight into LDS, without a register stage and without LDS store instructions: one
+  // global_load_lds_dwordx4 moves 64 lanes x 16 bytes to 1 KiB of LDS in lane order (M0 = LDS byte address), which is
+  // the layout of a packed fragment unit.  The copies are written as inline assembly so that the waits for them can be
+  // placed by hand: the compiler would wait for all of them at every LDS barrier.  They count in vmcnt like any load
+  // and complete in order; the kernel issues no other vector memory instruction before the end of the main loop.
+  // NB stage buffers: while k block s is multiplied, blocks s+1 .. s+NB-2 are in flight or have landed and block
+  // s+NB-1 is being requested.
+  constexpr int NB = PGEMM_NB;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const u32x4* srcA[4];
   const u32x4* srcB[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int f = wave + 4 * i;  // fragment 0..15 handled by this wavefront
-    srcA[i] = p.W + (int64_t)min(rg_tile + f, p.NRG - 1) * 64 + lane;
-    srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64 + lane;
+    const int f = wave_u + 4 * i;  // fragment unit 0..15 handled by this wavefront
+    srcA[i] = p.W + (int64_t)min(rg_tile + f, p.NRG - 1) * 64;
+    srcB[i] = p.X + ((int64_t)(tt * 8 + (f >> 1)) * K16 + (f & 1)) * 64;
   }
-  // Three register sets carry the memory requests of k blocks s+2 .. s+4, three LDS stage buffers hold k blocks
-  // s .. s+2, and two fragment sets carry the LDS reads of the two 16-column halves of a k block.
-  // Schedule of k block s (r = s mod 3):
-  //   first half : 16 MFMAs of half 0 (fragment set 0), one behind the other:
-  //                  8 memory requests for k block s+4            -> register set (r+1) mod 3
-  //                  8 LDS reads, half 1 of block s                -> fragment set 1
-  //                  4 LDS writes, weights of block s+2            (register set (r+2) mod 3 -> buffer (r+2) mod 3)
-  //   barrier that waits for LDS traffic only (the requests to memory stay in flight across it)
-  //   second half: 16 MFMAs of half 1 (fragment set 1), with
-  //                  8 LDS reads, half 0 of block s+1              -> fragment set 0
-  //                  4 LDS writes, activations of block s+2
-  // Every LDS read is issued 16 MFMAs before its data is needed, every memory request two k blocks before it is
-  // copied, and LDS reads + writes are the same 12 instructions in both halves (a two-buffer scheme must put all
-  // 8 writes into the first half, which then needs the whole LDS bandwidth).  Block s+2 is only read after the
-  // next barrier.  Past the last k block the requests are redirected to the last block; their copies are never read.
-  u32x4 ga0[4], gb0[4], ga1[4], gb1[4], ga2[4], gb2[4];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+  const uint32_t voff = lane * 16;
   u32x4 fa0[4], fb0[4], fa1[4], fb1[4];
   const int fm = lane & 31, fh = lane >> 5;
-  auto request = [&](u32x4(&ga)[4], u32x4(&gb)[4], int kb) __attribute__((always_inline)) {
+  auto dma16 = [&](const u32x4* g, uint32_t lds_addr) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+  };
+  // unit i = 0..7 of this wavefront's share of a k block: even = weights, odd = activations
+  auto stage1 = [&](int kbc, int buf, int i) __attribute__((always_inline)) {
+    const int q = i >> 1;
+    if (i & 1) dma16(srcB[q] + (int64_t)kbc * 128, lds0 + (uint32_t)(buf * 2048 + 1024 + (wave_u + 4 * q) * 64) * 16u);
+    else dma16(srcA[q] + (int64_t)kbc * p.NRG * 64, lds0 + (uint32_t)(buf * 2048 + (wave_u + 4 * q) * 64) * 16u);
+  };
+  auto stage = [&](int kb, int buf) __attribute__((always_inline)) {
     const int kbc = min(kb, p.KB - 1);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ga[i] = srcA[i][(int64_t)kbc * p.NRG * 64];
-      gb[i] = srcB[i][(int64_t)kbc * 128];
-    }
+    for (int i = 0; i < 8; ++i) stage1(kbc, buf, i);
   };
-  auto copy_a = [&](u32x4(&ga)[4], int buf) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) smem[buf * 2048 + (wave + 4 * i) * 64 + lane] = ga[i];
-  };
-  auto copy_b = [&](u32x4(&gb)[4], int buf) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) smem[buf * 2048 + 1024 + (wave + 4 * i) * 64 + lane] = gb[i];
+  // fragment read i = 0..7 of a 16-column half: 0..3 weights (row blocks), 4..7 activations (token blocks)
+  auto fetch1 = [&](u32x4(&fa)[4], u32x4(&fb)[4], int buf, int k16, int i) __attribute__((always_inline)) {
+    if (i < 4) fa[i] = smem[buf * 2048 + (wn * 8 + i * 2 + (fm >> 4)) * 64 + ((k16 * 2 + fh) << 4) + (fm & 15)];
+    else fb[i - 4] = smem[buf * 2048 + 1024 + ((wt * 4 + (i - 4)) * 2 + k16) * 64 + lane];
   };
   auto fetch = [&](u32x4(&fa)[4], u32x4(&fb)[4], int buf, int k16) __attribute__((always_inline)) {
-    const u32x4* A = smem + buf * 2048;
-    const u32x4* B = smem + buf * 2048 + 1024;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) fa[rb] = A[(wn * 8 + rb * 2 + (fm >> 4)) * 64 + ((k16 * 2 + fh) << 4) + (fm & 15)];
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb) fb[tb] = B[((wt * 4 + tb) * 2 + k16) * 64 + lane];
+    for (int i = 0; i < 8; ++i) fetch1(fa, fb, buf, k16, i);
   };
-  auto mfma16 = [&](u32x4(&fa)[4], u32x4(&fb)[4]) __attribute__((always_inline)) {
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb)
-        acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fa[rb]), as_f16x8(fb[tb]), acc[rb][tb], 0, 0, 0);
+  auto mfma1 = [&](u32x4(&fa)[4], u32x4(&fb)[4], int i) __attribute__((always_inline)) {
+    const int rb = i >> 2, tb = i & 3;
+    acc[rb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fa[rb]), as_f16x8(fb[tb]), acc[rb][tb], 0, 0, 0);
   };
   auto lds_barrier = [&]() __attribute__((always_inline)) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   };
-  // sched_group_barrier masks: 0x008 MFMA, 0x020 memory read, 0x100 LDS read, 0x200 LDS write
-  // r = s mod 3 selects the buffers; the register sets are passed in the matching rotation
-  auto k_block = [&](u32x4(&ga_req)[4], u32x4(&gb_req)[4], u32x4(&ga_cp)[4], u32x4(&gb_cp)[4], int s, int r) __attribute__((always_inline)) {
-    const int buf = r, buf1 = r == 2 ? 0 : r + 1, buf2 = r == 0 ? 2 : r - 1;
-    request(ga_req, gb_req, s + 4);
-    fetch(fa1, fb1, buf, 1);
-    copy_a(ga_cp, buf2);
-    mfma16(fa0, fb0);
+  // k block s sits in buffer r = s mod NB; two fragment sets carry the LDS reads of its two 16-column halves.  The
+  // instruction order is fixed by hand: one LDS read behind each of the first eight MFMAs of a half (half 1 of block s
+  // in the first half, half 0 of block s+1 in the second, each 8 to 16 MFMAs before its data is needed) and one stage
+  // copy behind every fourth MFMA, so that the requests of the four wavefronts reach the memory pipeline evenly spread.
+  // The copies of block s+NB-1 go to the buffer of block s-1, which nobody reads any more once the barrier of block
+  // s-1 has been passed.  One barrier per k block, in the middle: in front of it a wavefront waits until its own units
+  // of block s+1 have landed (at most (NB-3) blocks of 8 units and the 4 units of block s+NB-1 requested so far may
+  // still be outstanding); behind it everybody's have.  Past the last k block the copies are redirected to the last
+  // block; nobody reads them.
+  // s_waitcnt immediates for "at most n memory requests outstanding": a 6-bit count split over bits 3:0 and 15:14, the
+  // other counters unconstrained
+  constexpr int VM_MID = (NB - 3) * 8 + 4;
+  constexpr int WAIT_MID = 0x0F70 | (VM_MID & 15) | ((VM_MID >> 4) << 14);
+  constexpr int VM_PRO = (NB - 2) * 8;
+  constexpr int WAIT_PRO = 0x0F70 | (VM_PRO & 15) | ((VM_PRO >> 4) << 14);
+  auto k_block = [&](int s, int r) __attribute__((always_inline)) {
+    const int buf1 = r == NB - 1 ? 0 : r + 1, bufp = r == 0 ? NB - 1 : r - 1;
+    const int kbc = min(s + NB - 1, p.KB - 1);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    for (int i = 0; i < 16; ++i) {
+      mfma1(fa0, fb0, i);
+      if (i < 8) fetch1(fa1, fb1, r, 1, i);
+      if ((i & 3) == 3) stage1(kbc, bufp, i >> 2);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_waitcnt(WAIT_MID);  // this wavefront's units of block s+1 have landed
+    lds_barrier();                         // ... everybody's
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    for (int i = 0; i < 16; ++i) {
+      mfma1(fa1, fb1, i);
+      if (i < 8) fetch1(fa0, fb0, buf1, 0, i);
+      if ((i & 3) == 3) stage1(kbc, bufp, 4 + (i >> 2));
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    lds_barrier();
-    fetch(fa0, fb0, buf1, 0);
-    copy_b(gb_cp, buf2);
-    mfma16(fa1, fb1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < 4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
   };
 
-  request(ga0, gb0, 0);
-  request(ga1, gb1, 1);
-  request(ga2, gb2, 2);
-  copy_a(ga0, 0);
-  copy_b(gb0, 0);
-  copy_a(ga1, 1);
-  copy_b(gb1, 1);
-  request(ga0, gb0, 3);
+#pragma unroll
+  for (int b = 0; b < NB - 1; ++b) stage(b, b);
+  __builtin_amdgcn_s_waitcnt(WAIT_PRO);
   lds_barrier();
   fetch(fa0, fb0, 0, 0);
   {
-    // k block s requests block s+4 into set (s+1) mod 3 and copies block s+2 out of set (s+2) mod 3
     int s = 0;
-    for (; s + 2 < p.KB; s += 3) {
-      k_block(ga1, gb1, ga2, gb2, s, 0);
-      k_block(ga2, gb2, ga0, gb0, s + 1, 1);
-      k_block(ga0, gb0, ga1, gb1, s + 2, 2);
+    for (; s + NB - 1 < p.KB; s += NB) {
+#pragma unroll
+      for (int r = 0; r < NB; ++r) k_block(s + r, r);
     }
-    if (s < p.KB) k_block(ga1, gb1, ga2, gb2, s, 0);
-    if (s + 1 < p.KB) k_block(ga2, gb2, ga0, gb0, s + 1, 1);
+#pragma unroll
+    for (int r = 0; r < NB - 1; ++r)
+      if (s + r < p.KB) k_block(s + r, r);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the redirected copies past the last k block have landed too
   __syncthreads();  // the staging buffers are dead from here on; the residual epilogue reuses them
   float(*red_ssq)[256] = reinterpret_cast<float(*)[256]>(smem);
   (void)red_ssq;
