@@ -527,8 +527,8 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-template <int HD, int GH>
-__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
+template <int HD, int GH, int HG>
+__global__ __launch_bounds__(256 * HG, 2 / HG) void prefill_attn_kernel(const uint16_t* __restrict__ qp, const uint16_t* __restrict__ kplane,
                                                             const uint16_t* __restrict__ vplane, const float* __restrict__ kvscale,
                                                             const int32_t* __restrict__ q_lens,
                                                             const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ table,
@@ -538,13 +538,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
                                                             uint16_t* __restrict__ op) {
   constexpr int NKF = HD / 32, NVF = HD / 16;
   constexpr int CH = NKF * 64;         // 16-byte units of one block's keys (and of one block's values)
-  constexpr int NLD = 4 * CH / 256;    // units each thread moves per pair
+  constexpr int NT = 256 * HG;         // threads: HG groups of four wavefronts, each group with its own GH query heads
+  constexpr int NLD = 4 * CH / NT;     // units each thread moves per pair
   __shared__ u32x4 kv[2][4 * CH];      // per pair: keys of block 0, keys of block 1, values of block 0, values of block 1
   const int tile = blockIdx.x;
   if (tile >= meta[0]) return;
   const int j = blockIdx.y;
-  const int h0 = j * G + blockIdx.z * GH;  // first query head handled here
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = (tid >> 6) & 3, lane = tid & 63;
+  const int h0 = j * G + (blockIdx.z * HG + (tid >> 8)) * GH;  // first query head handled by this wavefront
   const int n = lane & 15, g = lane >> 4;
   const int b = tile_seq[tile];
   const int qlen = q_lens[b], ctx = seq_lens[b];
@@ -583,7 +584,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
   const int64_t blk_elems = (int64_t)KV_BS * HD;
   u32x4 stg[NLD];
   // units 0 .. NLD/2-1 of a thread are keys (one token per unit: one scale), the others values (four tokens per unit)
-  static_assert(NLD % 2 == 0 && (NLD / 2) * 256 == 2 * CH, "the first half of a thread's units are keys");
+  static_assert(NLD % 2 == 0 && (NLD / 2) * NT == 2 * CH, "the first half of a thread's units are keys");
   float ksc[NLD / 2];
   f32x4 vsc[NLD / 2];
   // Block ids are fetched one pair ahead of the request that uses them, so the request never waits for the table.
@@ -599,7 +600,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
     const int64_t off1 = ((int64_t)id1 * Hkv + j) * blk_elems;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int u = tid + i * 256, c = u / CH, within = u % CH;
+      const int u = tid + i * NT, c = u / CH, within = u % CH;
       const uint16_t* src = (c < 2 ? kplane : vplane) + ((c & 1) ? off1 : off0) + within * 8;
       stg[i] = *reinterpret_cast<const u32x4*>(src);
       const float* sc = kvscale + kv_scale_offset((c & 1) ? id1 : id0, Hkv, j);
@@ -622,7 +623,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const uint16_t* __
         const f16x2 h = __builtin_convertvector((f32x2){x0, x1}, f16x2);
         out[d] = __builtin_bit_cast(uint32_t, h);
       }
-      kv[buf][tid + i * 256] = out;
+      kv[buf][tid + i * NT] = out;
     }
   };
   // masked = false: every key of the pair is visible to every query of the wavefront (the pair ends at or before its
@@ -794,15 +795,21 @@ static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* v
   // two query heads per workgroup pass: their accumulators and operands fit 256 registers, so two workgroups share a
   // compute unit and one hides the other's softmax and LDS latencies (four heads per pass at one workgroup per unit: 1.5x slower)
   const int GH = (G % 2 == 0) ? 2 : 1;
-  dim3 grid(max_tiles, m->Hkv, G / GH), block(256);
+  // with 128-wide heads two such head groups form one workgroup of eight wavefronts (still two per SIMD) and share
+  // the copy of the keys and values into LDS, which halves the code-to-fp16 conversions per query head
+  const int HG = (HD == 128 && (G / GH) % 2 == 0) ? 2 : 1;
+  dim3 grid(max_tiles, m->Hkv, G / GH / HG), block(256 * HG);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const int32_t* cum_rows = m->meta + 16;
-#define PATTN(GH_)                                                                                                                 \
-  hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, kvscale, qlens, lens, \
+#define PATTN(GH_, HG_)                                                                                                            \
+  hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_, HG_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, kvscale, qlens, lens, \
                      table,                                                                                                        \
                      (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, G, m->tile_seq, m->tile_q0, m->meta, cum_rows, scale_log2,      \
                      (uint16_t*)m->op)
-  if (GH == 4) PATTN(4); else if (GH == 2) PATTN(2); else PATTN(1);
+  if constexpr (HD == 128) {
+    if (HG == 2) { PATTN(2, 2); return; }
+  }
+  if (GH == 2) PATTN(2, 1); else PATTN(1, 1);
 #undef PATTN
 }
 
