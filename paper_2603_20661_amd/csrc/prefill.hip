@@ -779,7 +779,7 @@ static void launch_pgemm(PGemmP& p, hipStream_t st) {
   p.n_tt = (p.T + 255) / 256;
   p.n_rt = (p.NRG + 15) / 16;
   if (p.wfactor == 0.f) p.wfactor = 1.f;  // not set: an unscaled matrix
-  static bool lds_enabled = false;  // per instantiation: allow 96 KiB of dynamic LDS
+  static bool lds_enabled = false;  // per instantiation: allow 128 KiB of dynamic LDS
   if (!lds_enabled) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_gemm_kernel<EPI, QKN>), hipFuncAttributeMaxDynamicSharedMemorySize,
                               PGEMM_LDS_BYTES);
