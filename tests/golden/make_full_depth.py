@@ -4,7 +4,7 @@ file format).  Calls only the CPU oracle and the seeded input generators; nothin
 
     python tests/golden/make_full_depth.py 1b | 8b | 8b-long | duel | mixed
 
-Run times on 8 host cores: 1b about 10 minutes, 8b 25, mixed 10, duel 35, 8b-long (one 4096-token prompt) 80.
+Run times on 8 host cores: 1b about 10 minutes, 8b 25, mixed 10, duel 35, 8b-long (one 4096-token prompt) 75.
 """
 from __future__ import annotations
 
