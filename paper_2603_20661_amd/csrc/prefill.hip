@@ -450,7 +450,9 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             float g = acc[rb][tb][q4 * 4 + i] * scale[tb], u = acc[rb][tb][(q4 + 2) * 4 + i] * scale[tb];
-            o.s[i] = f32_to_f16_sat(g / (1.f + __expf(-g)) * u);
+            // (hardware reciprocal, 1 ulp: the result is rounded to fp16 right away; a correctly rounded fp32 division
+            // costs ten instructions per element of the widest GEMM's epilogue)
+            o.s[i] = f32_to_f16_sat(g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u);
           }
           *reinterpret_cast<u32x2*>(p.ap + packed_p_offset(t, f0, p.Fp >> 4)) = o.v;
         }
