@@ -151,17 +151,33 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
 
-  // workgroup -> tile: consecutive ids on one XCD (ids are dealt round-robin to the 8 XCDs) walk
-  // groups of 8 token tiles so that an XCD's L2 sees few distinct weight / activation panels
-  int v = blockIdx.x;
+  // workgroup -> tile.  Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in order, so a round of 256
+  // workgroups gives every XCD 32 consecutive local indices.  Token tiles are taken in super-groups of 8 x GT: XCD x
+  // owns GT of them and walks the row tiles 8 at a time (32 workgroups = GT token tiles x 8 row tiles: its L2 sees
+  // GT + 8 operand panels per round), and all XCDs walk the row tiles in step, so a weight panel is fetched from
+  // memory once per super-group and found in the memory-side cache by the other seven.  The token tiles that do not
+  // fill a super-group follow in groups of GT with the ids' order simply transposed over the XCDs.
+  constexpr int GT = 4;
   const int total = p.n_tt * p.n_rt;
-  if (total % 8 == 0) v = (v % 8) * (total / 8) + v / 8;
-  const int GT = 8;
-  const int per_group = GT * p.n_rt;
-  const int group = v / per_group, first_tt = group * GT;
-  const int gsz = min(GT, p.n_tt - first_tt);
-  const int tt = first_tt + (v % per_group) % gsz;
-  const int rt = (v % per_group) / gsz;
+  const int n_sg = p.n_tt / (8 * GT);            // full super-groups
+  const int total_sg = n_sg * 8 * GT * p.n_rt;   // tiles in them (a multiple of 8)
+  int tt, rt;
+  if ((int)blockIdx.x < total_sg) {
+    const int x = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int per_sg = GT * p.n_rt;              // tiles of one XCD in one super-group
+    const int sg = li / per_sg, within = li % per_sg;
+    tt = (sg * 8 + x) * GT + within % GT;
+    rt = within / GT;
+  } else {
+    int v = blockIdx.x - total_sg;
+    const int rest = total - total_sg, tt0 = n_sg * 8 * GT;
+    if (rest % 8 == 0) v = (v % 8) * (rest / 8) + v / 8;
+    const int per_group = GT * p.n_rt;
+    const int group = v / per_group, first_tt = tt0 + group * GT;
+    const int gsz = min(GT, p.n_tt - first_tt);
+    tt = first_tt + (v % per_group) % gsz;
+    rt = (v % per_group) / gsz;
+  }
 
   const int rg_tile = rt * 16;
   const int t_tile = tt * 256;
@@ -537,17 +553,23 @@ __global__ __launch_bounds__(256 * HG, 2 / HG) void prefill_attn_kernel(const ui
                                                             int mbs, int Hq, int Hkv, int G, const int32_t* __restrict__ tile_seq,
                                                             const int32_t* __restrict__ tile_q0, const int32_t* __restrict__ meta,
                                                             const int32_t* __restrict__ cum_rows, float scale_log2,
-                                                            uint16_t* __restrict__ op) {
+                                                            uint16_t* __restrict__ op, int max_tiles) {
   constexpr int NKF = HD / 32, NVF = HD / 16;
   constexpr int CH = NKF * 64;         // 16-byte units of one block's keys (and of one block's values)
   constexpr int NT = 256 * HG;         // threads: HG groups of four wavefronts, each group with its own GH query heads
   constexpr int NLD = 4 * CH / NT;     // units each thread moves per pair
   __shared__ u32x4 kv[2][4 * CH];      // per pair: keys of block 0, keys of block 1, values of block 0, values of block 1
-  const int tile = blockIdx.x;
+  // Work items in the order (head group, kv head, tile), tiles fastest; workgroup ids are dealt round-robin to the 8
+  // XCDs, so the ids are transposed: XCD x gets the x-th eighth of that order, i.e. the consecutive tiles of a
+  // sequence and kv head run behind one L2 and fetch its keys and values into it once (with 8 kv heads: one per XCD).
+  int item = blockIdx.x;
+  const int n_items = gridDim.x;
+  if (n_items % 8 == 0) item = (item & 7) * (n_items >> 3) + (item >> 3);
+  const int tile = item % max_tiles;
   if (tile >= meta[0]) return;
-  const int j = blockIdx.y;
+  const int j = (item / max_tiles) % Hkv;
   const int tid = threadIdx.x, wave = (tid >> 6) & 3, lane = tid & 63;
-  const int h0 = j * G + (blockIdx.z * HG + (tid >> 8)) * GH;  // first query head handled by this wavefront
+  const int h0 = j * G + ((item / (max_tiles * Hkv)) * HG + (tid >> 8)) * GH;  // first query head handled by this wavefront
   const int n = lane & 15, g = lane >> 4;
   const int b = tile_seq[tile];
   const int qlen = q_lens[b], ctx = seq_lens[b];
@@ -800,14 +822,14 @@ static void launch_pattn(www_model* m, const uint16_t* kplane, const uint16_t* v
   // with 128-wide heads two such head groups form one workgroup of eight wavefronts (still two per SIMD) and share
   // the copy of the keys and values into LDS, which halves the code-to-fp16 conversions per query head
   const int HG = (HD == 128 && (G / GH) % 2 == 0) ? 2 : 1;
-  dim3 grid(max_tiles, m->Hkv, G / GH / HG), block(256 * HG);
+  dim3 grid(max_tiles * m->Hkv * (G / GH / HG)), block(256 * HG);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const int32_t* cum_rows = m->meta + 16;
 #define PATTN(GH_, HG_)                                                                                                            \
   hipLaunchKernelGGL((prefill_attn_kernel<HD, GH_, HG_>), grid, block, 0, st, (const uint16_t*)m->qp, kplane, vplane, kvscale, qlens, lens, \
                      table,                                                                                                        \
                      (int)m->cfg.max_blocks_per_seq, m->Hq, m->Hkv, G, m->tile_seq, m->tile_q0, m->meta, cum_rows, scale_log2,      \
-                     (uint16_t*)m->op)
+                     (uint16_t*)m->op, max_tiles)
   if constexpr (HD == 128) {
     if (HG == 2) { PATTN(2, 2); return; }
   }
