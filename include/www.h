@@ -185,6 +185,12 @@ int www_debug_profile_read(www_model* m, float* ms_host, int32_t* launches_host,
  * matrix-core rate of the GPU at hand, to set beside the published dense peak.  Errors: INVALID_ARG, HIP. */
 int www_debug_mfma_loop(int32_t workgroups, int32_t iters, float* sink_dev, double* flops_out, void* hip_stream);
 
+/* Test hook, host only (no GPU call): the tile that workgroup `workgroup` of a prefill projection GEMM over token_tiles x
+ * row_tiles tiles of 256 x 256 works on.  The order is laid out for the 8 L2 caches of the GPU (Sec. 3.2 names no kernel
+ * design; this is the library's own); what a test can check is that it visits every tile exactly once.  Outputs are
+ * host pointers.  Errors: INVALID_ARG (null pointers, counts below 1, workgroup outside [0, token_tiles * row_tiles)). */
+int www_debug_prefill_tile(int32_t workgroup, int32_t token_tiles, int32_t row_tiles, int32_t* token_tile_out, int32_t* row_tile_out);
+
 /* ------------------------------------------------------------------------------------------------
  * Duel bookkeeping (Sec. 4.2 "Duel-and-Judge Mechanism"; Sec. 5, Assumptions 2 and 3).
  *

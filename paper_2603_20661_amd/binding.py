@@ -21,7 +21,7 @@ EXPORTS = ("www_query_sizes", "www_model_load", "www_prefill", "www_decode_step"
            "www_judge_verdict", "www_ledger_create", "www_ledger_free", "www_ledger_stakes", "www_pos_sample", "www_ledger_serve",
            "www_ledger_duel", "www_ledger_num_ops", "www_ledger_read_ops",
            "www_sched_create", "www_sched_free", "www_sched_submit", "www_sched_plan", "www_sched_table_row", "www_sched_commit",
-           "www_get_stats", "www_sample_top_p", "www_sample_top_p_static", "www_check", "www_debug_mfma_loop")
+           "www_get_stats", "www_sample_top_p", "www_sample_top_p_static", "www_check", "www_debug_mfma_loop", "www_debug_prefill_tile")
 FLAG_QK_NORM = 1
 OP_BASE_REWARD, OP_DUEL_REWARD, OP_DUEL_PENALTY, OP_JUDGE_REWARD = 0, 1, 2, 3
 
@@ -81,6 +81,8 @@ def _load_library():
     L.www_last_error.restype = ctypes.c_char_p
     L.www_debug_mfma_loop.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.www_debug_mfma_loop.restype = ctypes.c_int
+    L.www_debug_prefill_tile.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    L.www_debug_prefill_tile.restype = ctypes.c_int
     L.www_check.argtypes = [vp, vp]
     L.www_check.restype = ctypes.c_int
     L.www_debug_slots.argtypes = [vp, vp, i32, vp, vp]
@@ -205,6 +207,13 @@ def www_debug_mfma_loop(workgroups: int, iters: int, sink, stream=None) -> float
     flops = ctypes.c_double()
     _check(lib.www_debug_mfma_loop(workgroups, iters, _ptr(sink, torch.float32), ctypes.byref(flops), _stream(stream)))
     return flops.value
+
+
+def www_debug_prefill_tile(workgroup: int, token_tiles: int, row_tiles: int):
+    """(token tile, row tile) that a workgroup of the prefill GEMM works on; host only"""
+    tt, rt = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib.www_debug_prefill_tile(workgroup, token_tiles, row_tiles, ctypes.byref(tt), ctypes.byref(rt)))
+    return tt.value, rt.value
 
 
 def www_check(model: Model, stream=None):

@@ -142,6 +142,37 @@ struct PGemmP {
   int Fp;
 };
 
+// Workgroup id -> tile of the prefill GEMM.  Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in order,
+// so a round of 256 workgroups gives every XCD 32 consecutive local indices.  Token tiles are taken in super-groups of
+// 8 x GT: XCD x owns GT of them and walks the row tiles 8 at a time (32 workgroups = GT token tiles x 8 row tiles: its
+// L2 sees GT + 8 operand panels per round), and all XCDs walk the row tiles in step, so a weight panel is fetched from
+// memory once per super-group and found in the memory-side cache by the other seven.  The token tiles that do not
+// fill a super-group follow in groups of GT with the ids' order simply transposed over the XCDs.  The map is a
+// bijection from [0, n_tt * n_rt) onto the tiles (checked on the host for many shapes through www_debug_prefill_tile).
+__host__ __device__ __forceinline__ void pgemm_tile_of(int id, int n_tt, int n_rt, int* tt_out, int* rt_out) {
+  constexpr int GT = 4;
+  const int total = n_tt * n_rt;
+  const int n_sg = n_tt / (8 * GT);            // full super-groups
+  const int total_sg = n_sg * 8 * GT * n_rt;   // tiles in them (a multiple of 8)
+  if (id < total_sg) {
+    const int x = id & 7, li = id >> 3;
+    const int per_sg = GT * n_rt;              // tiles of one XCD in one super-group
+    const int sg = li / per_sg, within = li % per_sg;
+    *tt_out = (sg * 8 + x) * GT + within % GT;
+    *rt_out = within / GT;
+  } else {
+    int v = id - total_sg;
+    const int rest = total - total_sg, tt0 = n_sg * 8 * GT;
+    if (rest % 8 == 0) v = (v % 8) * (rest / 8) + v / 8;
+    const int per_group = GT * n_rt;
+    const int group = v / per_group, first_tt = tt0 + group * GT;
+    const int left = n_tt - first_tt;
+    const int gsz = left < GT ? left : GT;
+    *tt_out = first_tt + (v % per_group) % gsz;
+    *rt_out = (v % per_group) / gsz;
+  }
+}
+
 // QKN: the QKV epilogue also normalises the query and key heads (an instantiation of its own, so that the plain model's
 // kernel carries none of its registers)
 template <int EPI, bool QKN = false>
@@ -151,33 +182,8 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(const PGemmP p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wn = wave >> 1, wt = wave & 1;
 
-  // workgroup -> tile.  Workgroup ids are dealt round-robin to the 8 XCDs and dispatched in order, so a round of 256
-  // workgroups gives every XCD 32 consecutive local indices.  Token tiles are taken in super-groups of 8 x GT: XCD x
-  // owns GT of them and walks the row tiles 8 at a time (32 workgroups = GT token tiles x 8 row tiles: its L2 sees
-  // GT + 8 operand panels per round), and all XCDs walk the row tiles in step, so a weight panel is fetched from
-  // memory once per super-group and found in the memory-side cache by the other seven.  The token tiles that do not
-  // fill a super-group follow in groups of GT with the ids' order simply transposed over the XCDs.
-  constexpr int GT = 4;
-  const int total = p.n_tt * p.n_rt;
-  const int n_sg = p.n_tt / (8 * GT);            // full super-groups
-  const int total_sg = n_sg * 8 * GT * p.n_rt;   // tiles in them (a multiple of 8)
   int tt, rt;
-  if ((int)blockIdx.x < total_sg) {
-    const int x = blockIdx.x & 7, li = blockIdx.x >> 3;
-    const int per_sg = GT * p.n_rt;              // tiles of one XCD in one super-group
-    const int sg = li / per_sg, within = li % per_sg;
-    tt = (sg * 8 + x) * GT + within % GT;
-    rt = within / GT;
-  } else {
-    int v = blockIdx.x - total_sg;
-    const int rest = total - total_sg, tt0 = n_sg * 8 * GT;
-    if (rest % 8 == 0) v = (v % 8) * (rest / 8) + v / 8;
-    const int per_group = GT * p.n_rt;
-    const int group = v / per_group, first_tt = tt0 + group * GT;
-    const int gsz = min(GT, p.n_tt - first_tt);
-    tt = first_tt + (v % per_group) % gsz;
-    rt = (v % per_group) / gsz;
-  }
+  pgemm_tile_of((int)blockIdx.x, p.n_tt, p.n_rt, &tt, &rt);
 
   const int rg_tile = rt * 16;
   const int t_tile = tt * 256;
@@ -894,5 +900,20 @@ int run_prefill(www_model* m, const int32_t* tok, const int32_t* qlens, const in
     set_error("prefill launch failed: %s", hipGetErrorString(e));
     return WWW_E_HIP;
   }
+  return WWW_OK;
+}
+
+// Host-side view of the prefill GEMM's workgroup -> tile map (tests).
+extern "C" __attribute__((visibility("default"))) int www_debug_prefill_tile(int32_t workgroup, int32_t token_tiles, int32_t row_tiles, int32_t* token_tile_out,
+                                      int32_t* row_tile_out) {
+  if (!token_tile_out || !row_tile_out || token_tiles < 1 || row_tiles < 1 || workgroup < 0 ||
+      (int64_t)workgroup >= (int64_t)token_tiles * row_tiles || (int64_t)token_tiles * row_tiles > 0x7fffffff) {
+    set_error("www_debug_prefill_tile: arguments out of range");
+    return WWW_E_INVALID_ARG;
+  }
+  int tt, rt;
+  pgemm_tile_of(workgroup, token_tiles, row_tiles, &tt, &rt);
+  *token_tile_out = tt;
+  *row_tile_out = rt;
   return WWW_OK;
 }

@@ -59,3 +59,28 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert B.lib.www_debug_slots(None, None, 1, None, None) == B.E_INVALID_ARG
     assert b"NULL" in B.lib.www_last_error() or b"bad" in B.lib.www_last_error()
     B.lib.www_model_free(None)
+
+
+def test_prefill_gemm_tile_order_visits_every_tile_once():
+    """the workgroup -> tile map of the prefill projections (laid out for the GPU's eight L2 caches) is a bijection, for
+    tile counts that fill whole super-groups of 32 token tiles, for remainders, and for single rows and columns"""
+    shapes = [(314, 112), (314, 16), (314, 24), (1, 1), (1, 7), (9, 1), (2, 3), (32, 16), (33, 7), (5, 112), (64, 16),
+              (63, 24), (31, 5), (32, 1), (40, 12), (157, 8), (4, 64)]
+    for n_tt, n_rt in shapes:
+        seen = {B.www_debug_prefill_tile(w, n_tt, n_rt) for w in range(n_tt * n_rt)}
+        assert seen == {(t, r) for t in range(n_tt) for r in range(n_rt)}, (n_tt, n_rt)
+    # in a full super-group the 32 workgroups an XCD gets per round of 256 are 4 token tiles x 8 row tiles,
+    # and the eight XCDs work on the same 8 row tiles
+    n_tt, n_rt = 64, 16
+    for rnd in range(4):
+        per_xcd = {}
+        for w in range(256 * rnd, 256 * (rnd + 1)):
+            per_xcd.setdefault(w % 8, []).append(B.www_debug_prefill_tile(w, n_tt, n_rt))
+        rows = None
+        for x, tiles in per_xcd.items():
+            assert len({t for t, _ in tiles}) == 4 and len({r for _, r in tiles}) == 8, (rnd, x)
+            rows = rows or {r for _, r in tiles}
+            assert {r for _, r in tiles} == rows
+    for bad in ((-1, 4, 4), (16, 4, 4), (0, 0, 4), (0, 4, 0)):
+        with pytest.raises(Exception):
+            B.www_debug_prefill_tile(*bad)
